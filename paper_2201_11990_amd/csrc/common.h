@@ -1,0 +1,124 @@
+// Shared declarations of the gfx950 layer-slice library: element types, status
+// handling, launch bookkeeping.  Internal to the GPU library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mtnlg.h"
+
+namespace mtnlg {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// Storage <-> fp32.  float -> bf16 is round-to-nearest-even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename E> __device__ __forceinline__ E from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+// 8 consecutive elements as one unit (16 B for bf16, 32 B for float).
+template <typename E> struct Vec8 { E v[8]; };
+template <typename E> __device__ __forceinline__ void load8(const E *p, float (&out)[8]) {
+  if constexpr (sizeof(E) == 2) {
+    bf16x8 t = *reinterpret_cast<const bf16x8 *>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = (float)t[i];
+  } else {
+    f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+    f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { out[i] = a[i]; out[4 + i] = b[i]; }
+  }
+}
+template <typename E> __device__ __forceinline__ void store8(E *p, const float (&in)[8]) {
+  if constexpr (sizeof(E) == 2) {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = (bf16)in[i];
+    *reinterpret_cast<bf16x8 *>(p) = t;
+  } else {
+    f32x4 a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = in[i]; b[i] = in[4 + i]; }
+    *reinterpret_cast<f32x4 *>(p) = a;
+    *reinterpret_cast<f32x4 *>(p + 4) = b;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// GeLU in fp32.  tanh form: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))); erf form:
+// 0.5 z (1 + erf(z / sqrt 2)).
+__device__ __forceinline__ float gelu_f(float z, bool erf_form) {
+  if (erf_form) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+  float inner = 0.79788456080286536f * (z + 0.044715f * z * z * z);
+  return 0.5f * z * (1.0f + tanhf(inner));
+}
+__device__ __forceinline__ float gelu_grad_f(float z, bool erf_form) {
+  if (erf_form) {
+    float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
+    float pdf = __expf(-0.5f * z * z) * 0.39894228040143268f;
+    return cdf + z * pdf;
+  }
+  float inner = 0.79788456080286536f * (z + 0.044715f * z * z * z);
+  float th = tanhf(inner);
+  float dinner = 0.79788456080286536f * (1.0f + 3.0f * 0.044715f * z * z);
+  return 0.5f * (1.0f + th) + 0.5f * z * (1.0f - th * th) * dinner;
+}
+
+// ---- host side -------------------------------------------------------------
+// Brackets a launch with HIP events when per-class timing is on (profile.cpp).
+struct LaunchScope {
+  int cls;
+  hipStream_t stream;
+  long idx;  // slot in the record list, -1 when timing is off
+  LaunchScope(int cls_, hipStream_t s);
+  ~LaunchScope();
+};
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? MTNLG_OK : MTNLG_HIP_ERROR; }
+
+#define MTNLG_TRY(expr)            \
+  do {                             \
+    int st__ = (expr);             \
+    if (st__ != MTNLG_OK) return st__; \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// internal launchers shared between translation units
+int gemm_generic(int dtype, int layout, int64_t M, int64_t N, int64_t K, const void *A,
+                 const void *B, void *C, const void *bias, void *aux, uint32_t epi,
+                 hipStream_t stream);
+// returns MTNLG_UNSUPPORTED_SHAPE when the MFMA kernel cannot take this problem
+int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
+                   void *C, const void *bias, void *aux, uint32_t epi, hipStream_t stream);
+int attention_fwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
+                         void *a, float *lse, hipStream_t stream);
+int attention_bwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
+                         const void *a, const float *lse, const void *da, void *dqkv, void *ws,
+                         hipStream_t stream);
+
+// MFMA attention (bf16): which head sizes it takes, its scratch need, its launchers
+bool attention_mfma_supported(int dtype, int d);
+size_t attention_bwd_workspace_bytes(int b, int s, int n, int d);
+int attention_fwd_mfma(int b, int s, int n, int d, float scale, const void *qkv, void *a, float *lse,
+                       hipStream_t stream);
+int attention_bwd_mfma(int b, int s, int n, int d, float scale, const void *qkv, const void *a,
+                       const float *lse, const void *da, void *dqkv, void *ws, hipStream_t stream);
+
+}  // namespace mtnlg

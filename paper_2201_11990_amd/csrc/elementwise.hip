@@ -1,0 +1,470 @@
+// HBM-bound kernels of the layer: LayerNorm forward (optionally fused with the
+// bias + residual add that precedes it), LayerNorm backward, GeLU forward and
+// backward, bias + residual, and the column reductions that produce bias and
+// LayerNorm parameter gradients.  All arithmetic fp32; 16-byte (bf16) or
+// 32-byte (float) accesses per lane, consecutive lanes on consecutive addresses.
+#include "common.h"
+
+namespace mtnlg {
+
+// Sum over the 256 threads of a workgroup; result valid in every thread.
+__device__ __forceinline__ float block_sum_256(float v, float *lds4) {
+  v = wave_sum(v);
+  __syncthreads();  // protects lds4 against a previous use
+  if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+}
+
+// ---------------------------------------------------------------- LayerNorm fwd
+// One workgroup per token row; the row lives in registers (NV groups of 8 per
+// thread).  v = x (+ partial + bias); optional xsum = v; out = LN(v).
+template <typename E, int NV>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(int64_t h, const E *__restrict__ x,
+                                                     const E *__restrict__ partial,
+                                                     const E *__restrict__ bias,
+                                                     const E *__restrict__ gamma,
+                                                     const E *__restrict__ beta, float eps,
+                                                     E *__restrict__ xsum, E *__restrict__ out,
+                                                     float *__restrict__ mean,
+                                                     float *__restrict__ rstd) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.x;
+  const int nvec = (int)(h / 8);
+  float v[NV][8];
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int j = threadIdx.x + i * 256;
+    if (j < nvec) {
+      load8(x + row * h + (int64_t)j * 8, v[i]);
+      if (partial) {
+        float pa[8];
+        load8(partial + row * h + (int64_t)j * 8, pa);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[i][e] += pa[e];
+        if (bias) {
+          load8(bias + (int64_t)j * 8, pa);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[i][e] += pa[e];
+        }
+        if constexpr (sizeof(E) == 2) {
+          // the residual stream is stored in bf16: normalise the stored value
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[i][e] = to_f32(from_f32<E>(v[i][e]));
+        }
+        if (xsum) store8(xsum + row * h + (int64_t)j * 8, v[i]);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += v[i][e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = 0.0f;
+    }
+  }
+  const float mu = block_sum_256(s, red) / (float)h;
+  float q = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int j = threadIdx.x + i * 256;
+    if (j < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q += (v[i][e] - mu) * (v[i][e] - mu);
+    }
+  }
+  const float var = block_sum_256(q, red) / (float)h;
+  const float rs = rsqrtf(var + eps);
+  if (threadIdx.x == 0) {
+    mean[row] = mu;
+    rstd[row] = rs;
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int j = threadIdx.x + i * 256;
+    if (j < nvec) {
+      float g[8], b[8], o[8];
+      load8(gamma + (int64_t)j * 8, g);
+      load8(beta + (int64_t)j * 8, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = g[e] * ((v[i][e] - mu) * rs) + b[e];
+      store8(out + row * h + (int64_t)j * 8, o);
+    }
+  }
+}
+
+template <typename E>
+static int ln_fwd_launch(int64_t T, int64_t h, const void *x, const void *partial, const void *bias,
+                         const void *gamma, const void *beta, float eps, void *xsum, void *out,
+                         float *mean, float *rstd, hipStream_t st) {
+  const int nv = (int)((h / 8 + 255) / 256);
+#define LNF(NV)                                                                                   \
+  ln_fwd_kernel<E, NV><<<dim3((unsigned)T), 256, 0, st>>>(                                        \
+      h, (const E *)x, (const E *)partial, (const E *)bias, (const E *)gamma, (const E *)beta, eps, \
+      (E *)xsum, (E *)out, mean, rstd)
+  LaunchScope scope(MTNLG_K_LN_FWD, st);
+  if (nv <= 1) LNF(1);
+  else if (nv <= 2) LNF(2);
+  else if (nv <= 4) LNF(4);
+  else if (nv <= 8) LNF(8);
+  else if (nv <= 16) LNF(16);
+  else return MTNLG_UNSUPPORTED_SHAPE;
+#undef LNF
+  return check_launch();
+}
+
+// ---------------------------------------------------------------- LayerNorm bwd
+// Row part: dx = dres + rs * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dout * gamma.
+template <typename E, int NV>
+__global__ __launch_bounds__(256) void ln_bwd_row_kernel(int64_t h, const E *__restrict__ x,
+                                                         const E *__restrict__ gamma,
+                                                         const float *__restrict__ mean,
+                                                         const float *__restrict__ rstd,
+                                                         const E *__restrict__ dout,
+                                                         const E *__restrict__ dres,
+                                                         E *__restrict__ dx) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.x;
+  const int nvec = (int)(h / 8);
+  const float mu = mean[row], rs = rstd[row];
+  float xh[NV][8], dh[NV][8];
+  float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int j = threadIdx.x + i * 256;
+    if (j < nvec) {
+      float g[8];
+      load8(x + row * h + (int64_t)j * 8, xh[i]);
+      load8(dout + row * h + (int64_t)j * 8, dh[i]);
+      load8(gamma + (int64_t)j * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        xh[i][e] = (xh[i][e] - mu) * rs;
+        dh[i][e] *= g[e];
+        s1 += dh[i][e];
+        s2 += dh[i][e] * xh[i][e];
+      }
+    }
+  }
+  const float m1 = block_sum_256(s1, red) / (float)h;
+  const float m2 = block_sum_256(s2, red) / (float)h;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int j = threadIdx.x + i * 256;
+    if (j < nvec) {
+      float o[8], r[8];
+      if (dres) load8(dres + row * h + (int64_t)j * 8, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        o[e] = (dres ? r[e] : 0.0f) + rs * (dh[i][e] - m1 - xh[i][e] * m2);
+      store8(dx + row * h + (int64_t)j * 8, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- column reductions
+// Stage 1: workgroup (bx, by) owns 512 columns [bx*512, +512) and the rows
+// t = by*4 + wave, stepping by 4*gridDim.y.  Lane l owns columns 8l..8l+7 of
+// the strip.  MODE 0: sum of in.  MODE 1 (LayerNorm): out0 = sum dout*xhat,
+// out1 = sum dout, and, if dx != NULL, out2 = sum dx.
+// Partials land in ws as [nout][gridDim.y][C] floats; stage 2 adds them up in a
+// fixed order, so results do not depend on scheduling.
+constexpr int CR_COLS = 512;
+
+template <typename E, int MODE>
+__global__ __launch_bounds__(256) void colreduce_stage1(int64_t T, int64_t C,
+                                                        const E *__restrict__ in,
+                                                        const E *__restrict__ x,
+                                                        const float *__restrict__ mean,
+                                                        const float *__restrict__ rstd,
+                                                        const E *__restrict__ dx,
+                                                        float *__restrict__ ws) {
+  constexpr int NOUT = MODE == 0 ? 1 : 3;
+  __shared__ float red[4][NOUT][CR_COLS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c0 = (int64_t)blockIdx.x * CR_COLS + lane * 8;
+  float acc[NOUT][8] = {};
+  if (c0 < C) {
+    for (int64_t t = (int64_t)blockIdx.y * 4 + wave; t < T; t += 4 * (int64_t)gridDim.y) {
+      float a[8];
+      load8(in + t * C + c0, a);
+      if constexpr (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[0][e] += a[e];
+      } else {
+        float xv[8];
+        load8(x + t * C + c0, xv);
+        const float mu = mean[t], rs = rstd[t];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          acc[0][e] += a[e] * ((xv[e] - mu) * rs);
+          acc[1][e] += a[e];
+        }
+        if (dx) {
+          load8(dx + t * C + c0, xv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[2][e] += xv[e];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 0; o < NOUT; ++o)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[wave][o][lane * 8 + e] = acc[o][e];
+  __syncthreads();
+  for (int i = threadIdx.x; i < NOUT * CR_COLS; i += 256) {
+    int o = i / CR_COLS, c = i % CR_COLS;
+    int64_t col = (int64_t)blockIdx.x * CR_COLS + c;
+    if (col < C) {
+      float s = red[0][o][c] + red[1][o][c] + red[2][o][c] + red[3][o][c];
+      ws[((int64_t)o * gridDim.y + blockIdx.y) * C + col] = s;
+    }
+  }
+}
+
+// Stage 2: out[c] (+)= sum_r ws[o][r][c]
+template <typename O>
+__global__ void colreduce_stage2(int64_t C, int nrb, const float *__restrict__ ws, O *out,
+                                 int accumulate) {
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  float s = 0.0f;
+  for (int r = 0; r < nrb; ++r) s += ws[(int64_t)r * C + c];
+  if (accumulate) s += to_f32(out[c]);
+  out[c] = from_f32<O>(s);
+}
+
+static int colreduce_rowblocks(int64_t T) {
+  int64_t rb = (T + 63) / 64;  // at least 16 rows per wave
+  if (rb < 1) rb = 1;
+  if (rb > 32) rb = 32;
+  return (int)rb;
+}
+
+template <typename E>
+static void stage2_launch(int64_t C, int nrb, const float *ws, void *out, int out_f32, int accumulate,
+                          hipStream_t st) {
+  dim3 grid((unsigned)((C + 255) / 256));
+  if (out_f32)
+    colreduce_stage2<float><<<grid, 256, 0, st>>>(C, nrb, ws, (float *)out, accumulate);
+  else
+    colreduce_stage2<E><<<grid, 256, 0, st>>>(C, nrb, ws, (E *)out, accumulate);
+}
+
+template <typename E>
+static int ln_bwd_launch(int64_t T, int64_t h, const void *x, const void *gamma, const float *mean,
+                         const float *rstd, const void *dout, const void *dres, void *dx,
+                         void *dgamma, void *dbeta, void *colsum_dx, int grad_f32, int accumulate,
+                         void *workspace, hipStream_t st) {
+  const int nv = (int)((h / 8 + 255) / 256);
+#define LNB(NV)                                                                          \
+  ln_bwd_row_kernel<E, NV><<<dim3((unsigned)T), 256, 0, st>>>(                           \
+      h, (const E *)x, (const E *)gamma, mean, rstd, (const E *)dout, (const E *)dres, (E *)dx)
+  {
+    LaunchScope scope(MTNLG_K_LN_BWD, st);
+    if (nv <= 1) LNB(1);
+    else if (nv <= 2) LNB(2);
+    else if (nv <= 4) LNB(4);
+    else if (nv <= 8) LNB(8);
+    else if (nv <= 16) LNB(16);
+    else return MTNLG_UNSUPPORTED_SHAPE;
+    MTNLG_TRY(check_launch());
+  }
+#undef LNB
+  const int nrb = colreduce_rowblocks(T);
+  float *ws = (float *)workspace;
+  dim3 grid((unsigned)((h + CR_COLS - 1) / CR_COLS), (unsigned)nrb);
+  {
+    LaunchScope scope(MTNLG_K_LN_BWD, st);
+    colreduce_stage1<E, 1><<<grid, 256, 0, st>>>(T, h, (const E *)dout, (const E *)x, mean, rstd,
+                                                 colsum_dx ? (const E *)dx : nullptr, ws);
+    MTNLG_TRY(check_launch());
+  }
+  LaunchScope scope(MTNLG_K_LN_BWD, st);
+  stage2_launch<E>(h, nrb, ws, dgamma, grad_f32, accumulate, st);
+  stage2_launch<E>(h, nrb, ws + (int64_t)nrb * h, dbeta, grad_f32, accumulate, st);
+  if (colsum_dx) stage2_launch<E>(h, nrb, ws + 2 * (int64_t)nrb * h, colsum_dx, grad_f32, accumulate, st);
+  return check_launch();
+}
+
+template <typename E>
+static int colsum_launch(int64_t T, int64_t C, const void *in, void *out, int out_f32, int accumulate,
+                         void *workspace, hipStream_t st) {
+  const int nrb = colreduce_rowblocks(T);
+  dim3 grid((unsigned)((C + CR_COLS - 1) / CR_COLS), (unsigned)nrb);
+  LaunchScope scope(MTNLG_K_COLSUM, st);
+  colreduce_stage1<E, 0><<<grid, 256, 0, st>>>(T, C, (const E *)in, nullptr, nullptr, nullptr, nullptr,
+                                               (float *)workspace);
+  MTNLG_TRY(check_launch());
+  stage2_launch<E>(C, nrb, (const float *)workspace, out, out_f32, accumulate, st);
+  return check_launch();
+}
+
+// ---------------------------------------------------------------- GeLU / residual
+template <typename E>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(int64_t nvec, const E *__restrict__ z,
+                                                       E *__restrict__ g, int erf_form) {
+  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nvec; j += (int64_t)gridDim.x * 256) {
+    float v[8];
+    load8(z + j * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e], erf_form != 0);
+    store8(g + j * 8, v);
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t nvec, const E *__restrict__ z,
+                                                       const E *dg, E *dz, int erf_form) {
+  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nvec; j += (int64_t)gridDim.x * 256) {
+    float v[8], d[8];
+    load8(z + j * 8, v);
+    load8(dg + j * 8, d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d[e] *= gelu_grad_f(v[e], erf_form != 0);
+    store8(dz + j * 8, d);
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void bias_residual_kernel(int64_t T, int64_t h,
+                                                            const E *__restrict__ res,
+                                                            const E *__restrict__ partial,
+                                                            const E *__restrict__ bias,
+                                                            E *__restrict__ out) {
+  const int64_t hv = h / 8, nvec = T * hv;
+  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nvec; j += (int64_t)gridDim.x * 256) {
+    float a[8], b[8];
+    load8(res + j * 8, a);
+    load8(partial + j * 8, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] += b[e];
+    if (bias) {
+      load8(bias + (j % hv) * 8, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] += b[e];
+    }
+    store8(out + j * 8, a);
+  }
+}
+
+static unsigned ew_grid(int64_t nvec) {
+  int64_t g = (nvec + 255) / 256;
+  if (g > 256 * 16) g = 256 * 16;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+
+}  // namespace mtnlg
+
+using namespace mtnlg;
+
+extern "C" {
+
+int mtnlg_layernorm_fwd(int dtype, int64_t T, int64_t h, const void *x, const void *partial,
+                        const void *bias, const void *gamma, const void *beta, float eps, void *xsum,
+                        void *out, float *mean, float *rstd, void *stream) {
+  if (!x || !gamma || !beta || !out || !mean || !rstd) return MTNLG_NULL_POINTER;
+  if (T <= 0 || h <= 0) return MTNLG_INVALID_ARG;
+  if (h % 8 || h > 32768) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MTNLG_F32)
+    return ln_fwd_launch<float>(T, h, x, partial, bias, gamma, beta, eps, xsum, out, mean, rstd, st);
+  if (dtype == MTNLG_BF16)
+    return ln_fwd_launch<bf16>(T, h, x, partial, bias, gamma, beta, eps, xsum, out, mean, rstd, st);
+  return MTNLG_INVALID_ARG;
+}
+
+size_t mtnlg_layernorm_bwd_workspace(int64_t T, int64_t h) {
+  if (T <= 0 || h <= 0) return 0;
+  return (size_t)3 * colreduce_rowblocks(T) * (size_t)h * sizeof(float);
+}
+
+int mtnlg_layernorm_bwd(int dtype, int64_t T, int64_t h, const void *x, const void *gamma,
+                        const float *mean, const float *rstd, const void *dout, const void *dres,
+                        void *dx, void *dgamma, void *dbeta, void *colsum_dx, int grad_f32,
+                        int accumulate, void *workspace, void *stream) {
+  if (!x || !gamma || !mean || !rstd || !dout || !dx || !dgamma || !dbeta || !workspace)
+    return MTNLG_NULL_POINTER;
+  if (T <= 0 || h <= 0) return MTNLG_INVALID_ARG;
+  if (h % 8 || h > 32768) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MTNLG_F32)
+    return ln_bwd_launch<float>(T, h, x, gamma, mean, rstd, dout, dres, dx, dgamma, dbeta, colsum_dx,
+                                1, accumulate, workspace, st);
+  if (dtype == MTNLG_BF16)
+    return ln_bwd_launch<bf16>(T, h, x, gamma, mean, rstd, dout, dres, dx, dgamma, dbeta, colsum_dx,
+                               grad_f32, accumulate, workspace, st);
+  return MTNLG_INVALID_ARG;
+}
+
+int mtnlg_gelu_fwd(int dtype, int gelu, int64_t count, const void *z, void *g, void *stream) {
+  if (!z || !g) return MTNLG_NULL_POINTER;
+  if (count <= 0 || (gelu != 0 && gelu != 1)) return MTNLG_INVALID_ARG;
+  if (count % 8) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  LaunchScope scope(MTNLG_K_GELU, st);
+  if (dtype == MTNLG_F32)
+    gelu_fwd_kernel<float><<<ew_grid(count / 8), 256, 0, st>>>(count / 8, (const float *)z, (float *)g, gelu);
+  else if (dtype == MTNLG_BF16)
+    gelu_fwd_kernel<bf16><<<ew_grid(count / 8), 256, 0, st>>>(count / 8, (const bf16 *)z, (bf16 *)g, gelu);
+  else
+    return MTNLG_INVALID_ARG;
+  return check_launch();
+}
+
+int mtnlg_gelu_bwd(int dtype, int gelu, int64_t count, const void *z, const void *dg, void *dz,
+                   void *stream) {
+  if (!z || !dg || !dz) return MTNLG_NULL_POINTER;
+  if (count <= 0 || (gelu != 0 && gelu != 1)) return MTNLG_INVALID_ARG;
+  if (count % 8) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  LaunchScope scope(MTNLG_K_GELU, st);
+  if (dtype == MTNLG_F32)
+    gelu_bwd_kernel<float><<<ew_grid(count / 8), 256, 0, st>>>(count / 8, (const float *)z,
+                                                               (const float *)dg, (float *)dz, gelu);
+  else if (dtype == MTNLG_BF16)
+    gelu_bwd_kernel<bf16><<<ew_grid(count / 8), 256, 0, st>>>(count / 8, (const bf16 *)z,
+                                                              (const bf16 *)dg, (bf16 *)dz, gelu);
+  else
+    return MTNLG_INVALID_ARG;
+  return check_launch();
+}
+
+size_t mtnlg_colsum_workspace(int64_t T, int64_t C) {
+  if (T <= 0 || C <= 0) return 0;
+  return (size_t)colreduce_rowblocks(T) * (size_t)C * sizeof(float);
+}
+
+int mtnlg_colsum(int dtype, int64_t T, int64_t C, const void *in, void *out, int out_f32,
+                 int accumulate, void *workspace, void *stream) {
+  if (!in || !out || !workspace) return MTNLG_NULL_POINTER;
+  if (T <= 0 || C <= 0) return MTNLG_INVALID_ARG;
+  if (C % 8) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MTNLG_F32) return colsum_launch<float>(T, C, in, out, 1, accumulate, workspace, st);
+  if (dtype == MTNLG_BF16) return colsum_launch<bf16>(T, C, in, out, out_f32, accumulate, workspace, st);
+  return MTNLG_INVALID_ARG;
+}
+
+int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const void *partial,
+                        const void *bias, void *out, void *stream) {
+  if (!res || !partial || !out) return MTNLG_NULL_POINTER;
+  if (T <= 0 || h <= 0) return MTNLG_INVALID_ARG;
+  if (h % 8) return MTNLG_UNSUPPORTED_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  LaunchScope scope(MTNLG_K_ELEMENTWISE, st);
+  if (dtype == MTNLG_F32)
+    bias_residual_kernel<float><<<ew_grid(T * h / 8), 256, 0, st>>>(T, h, (const float *)res,
+                                                                    (const float *)partial,
+                                                                    (const float *)bias, (float *)out);
+  else if (dtype == MTNLG_BF16)
+    bias_residual_kernel<bf16><<<ew_grid(T * h / 8), 256, 0, st>>>(T, h, (const bf16 *)res,
+                                                                   (const bf16 *)partial,
+                                                                   (const bf16 *)bias, (bf16 *)out);
+  else
+    return MTNLG_INVALID_ARG;
+  return check_launch();
+}
+
+}  // extern "C"

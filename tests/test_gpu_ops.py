@@ -1,0 +1,185 @@
+"""Kernel-level parity on the GPU: each exported operation against the oracle's matching piece,
+element by element, on shapes that span several tiles and leave a ragged tail."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2201_11990_amd as M
+from paper_2201_11990_amd import binding as B
+from parity import TOL, assert_close, dev, rel_fro, to_np
+
+pytestmark = pytest.mark.gpu
+DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
+
+
+def randn(shape, dtype, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * scale).to(DT[dtype])
+
+
+def gemm_oracle(layout, A, Bm, bias=None):
+    A, Bm = to_np(A), to_np(Bm)
+    if layout == B.GEMM_NT:
+        return oracle.linear_fwd(A, Bm, to_np(bias) if bias is not None else None)
+    if layout == B.GEMM_NN:
+        return oracle.linear_dgrad(A, Bm)
+    return oracle.linear_wgrad(A, Bm)[0]
+
+
+GEMM_SHAPES = [(64, 64, 64), (200, 136, 88), (264, 520, 328), (37, 53, 29), (8, 8, 8), (1000, 24, 4104),
+               (520, 776, 2056)]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("layout", [B.GEMM_NT, B.GEMM_NN, B.GEMM_TN])
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_plain(dtype, layout, shape):
+    Mm, N, K = shape
+    a_shape = (Mm, K) if layout != B.GEMM_TN else (K, Mm)
+    b_shape = (N, K) if layout == B.GEMM_NT else (K, N)
+    A, Bm = randn(a_shape, dtype, 1), randn(b_shape, dtype, 2)
+    C = torch.full((Mm, N), float("nan"), dtype=DT[dtype], device="cuda")
+    M.mtnlg_gemm(layout, dev(A), dev(Bm), C)
+    assert_close(C, gemm_oracle(layout, A, Bm), TOL[dtype], f"gemm {layout} {shape}")
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("shape", [(200, 136, 88), (264, 520, 328), (45, 27, 19)])
+def test_gemm_epilogues(dtype, shape):
+    Mm, N, K = shape
+    tol = TOL[dtype]
+    A, W, bias, res = randn((Mm, K), dtype, 3), randn((N, K), dtype, 4, 0.2), randn((N,), dtype, 5), randn((Mm, N), dtype, 6)
+    want = gemm_oracle(B.GEMM_NT, A, W, bias)
+    dA, dW, dbias, dres = map(dev, (A, W, bias, res))
+    # bias
+    C = torch.empty((Mm, N), dtype=DT[dtype], device="cuda")
+    M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, bias=dbias, epilogue=B.EPI_BIAS)
+    assert_close(C, want, tol, "bias")
+    # bias + GeLU (both forms): C = GeLU(z), aux = z
+    for erf_form in (False, True):
+        Z = torch.empty_like(C)
+        M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, bias=dbias, aux=Z,
+                     epilogue=B.EPI_BIAS | B.EPI_GELU | (B.EPI_GELU_ERF if erf_form else 0))
+        assert_close(Z, want, tol, "pre-activation")
+        assert_close(C, oracle.gelu(want, exact=erf_form), tol, f"gelu erf={erf_form}")
+    # bias + residual
+    M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, bias=dbias, aux=dres, epilogue=B.EPI_BIAS | B.EPI_RESIDUAL)
+    assert_close(C, want + to_np(res), tol, "bias+residual")
+    # accumulate into an existing buffer, and fp32 output from bf16 inputs
+    C.copy_(dres)
+    M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, epilogue=B.EPI_ACCUMULATE)
+    assert_close(C, gemm_oracle(B.GEMM_NT, A, W) + to_np(res), tol, "accumulate")
+    C32 = dres.float().contiguous()
+    M.mtnlg_gemm(B.GEMM_NT, dA, dW, C32, epilogue=B.EPI_ACCUMULATE | B.EPI_OUT_F32)
+    assert_close(C32, gemm_oracle(B.GEMM_NT, A, W) + to_np(res), 1e-5 if dtype == "fp32" else 1e-3, "acc f32")
+    C32.fill_(float("nan"))
+    M.mtnlg_gemm(B.GEMM_TN, dev(randn((K, Mm), dtype, 7)), dev(randn((K, N), dtype, 8)), C32, epilogue=B.EPI_OUT_F32)
+    assert_close(C32, gemm_oracle(B.GEMM_TN, randn((K, Mm), dtype, 7), randn((K, N), dtype, 8)), 1e-5, "tn f32 out")
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("T,h", [(5, 256), (33, 2056), (7, 20480), (3, 8)])
+def test_layernorm_fwd_bwd(dtype, T, h):
+    tol = TOL[dtype]
+    x = randn((T, h), dtype, 10, 2.0) + 0.5
+    x = x.to(DT[dtype])
+    gamma, beta = (1 + randn((h,), dtype, 11, 0.2).float()).to(DT[dtype]), randn((h,), dtype, 12, 0.2)
+    dout, dres = randn((T, h), dtype, 13), randn((T, h), dtype, 14)
+    out = torch.empty((T, h), dtype=DT[dtype], device="cuda")
+    mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
+    M.mtnlg_layernorm_fwd(dev(x), dev(gamma), dev(beta), 1e-5, out, mean, rstd)
+    o_out, o_mean, o_rstd = oracle.layernorm_fwd(to_np(x), to_np(gamma), to_np(beta), 1e-5)
+    assert_close(out, o_out, tol, "ln out")
+    assert_close(mean, o_mean, 1e-5, "ln mean")
+    assert_close(rstd, o_rstd, 1e-5, "ln rstd")
+    # fused x + partial + bias
+    partial, bias = randn((T, h), dtype, 15), randn((h,), dtype, 16)
+    xsum = torch.empty_like(out)
+    M.mtnlg_layernorm_fwd(dev(x), dev(gamma), dev(beta), 1e-5, out, mean, rstd, partial=dev(partial), bias=dev(bias), xsum=xsum)
+    s = to_np(x) + to_np(partial) + to_np(bias)
+    assert_close(xsum, s, tol, "xsum")
+    assert_close(out, oracle.layernorm_fwd(s, to_np(gamma), to_np(beta), 1e-5)[0], tol * 1.5, "ln(xsum)")
+    # backward with the oracle's stats on the original x
+    ws = torch.empty(M.mtnlg_layernorm_bwd_workspace(T, h), dtype=torch.uint8, device="cuda")
+    dx = torch.empty_like(out)
+    gdt = torch.float32
+    dgamma, dbeta, cs = (torch.full((h,), float("nan"), dtype=gdt, device="cuda") for _ in range(3))
+    M.mtnlg_layernorm_bwd(dev(x), dev(gamma), dev(torch.tensor(o_mean, dtype=torch.float32)),
+                          dev(torch.tensor(o_rstd, dtype=torch.float32)), dev(dout), dx, dgamma, dbeta, ws,
+                          dres=dev(dres), colsum_dx=cs, grad_f32=True)
+    o_dx, o_dg, o_db = oracle.layernorm_bwd(to_np(x), to_np(gamma), o_mean, o_rstd, to_np(dout))
+    assert_close(dx, o_dx + to_np(dres), tol, "ln dx")
+    assert_close(dgamma, o_dg, tol, "ln dgamma")
+    assert_close(dbeta, o_db, tol, "ln dbeta")
+    assert_close(cs, to_np(dx).sum(0), tol, "colsum dx")
+    # accumulate on top
+    M.mtnlg_layernorm_bwd(dev(x), dev(gamma), dev(torch.tensor(o_mean, dtype=torch.float32)),
+                          dev(torch.tensor(o_rstd, dtype=torch.float32)), dev(dout), dx, dgamma, dbeta, ws,
+                          grad_f32=True, accumulate=True)
+    assert_close(dgamma, 2 * o_dg, tol, "ln dgamma accumulated")
+    assert_close(dx, o_dx, tol, "ln dx without residual")
+
+
+ATT_CASES = [(2, 40, 3, 64), (1, 130, 2, 128), (2, 77, 2, 160), (1, 1, 1, 8), (1, 300, 1, 32), (1, 257, 2, 160)]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("b,s,n,d", ATT_CASES)
+def test_attention_fwd_bwd(dtype, b, s, n, d):
+    tol = TOL[dtype]
+    dims = oracle.Dims(hidden=8, heads=n, head_dim=d, ffn=8, seq=s, batch=b)
+    qkv = randn((b * s, 3 * n * d), dtype, 20, 1.0)
+    da = randn((b * s, n * d), dtype, 21)
+    scale = 1.0 / math.sqrt(d)
+    a = torch.full((b * s, n * d), float("nan"), dtype=DT[dtype], device="cuda")
+    lse = torch.empty((b, n, s), device="cuda")
+    M.mtnlg_attention_fwd(b, s, n, d, scale, dev(qkv), a, lse)
+    o_a, P = oracle.attention_fwd(dims, to_np(qkv), return_probs=True)
+    assert_close(a, o_a, tol, "attention out")
+    # log-sum-exp of the scaled masked scores, from the definition
+    q = to_np(qkv).reshape(b, s, n, 3, d)
+    S = np.einsum("bsnd,btnd->bnst", q[:, :, :, 0], q[:, :, :, 1]) * scale
+    S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    want_lse = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(to_np(lse) - want_lse).max() < 1e-3 + 2e-3 * (dtype == "bf16")
+    ws = torch.empty(M.mtnlg_attention_bwd_workspace(b, s, n, d), dtype=torch.uint8, device="cuda")
+    dqkv = torch.full(qkv.shape, float("nan"), dtype=DT[dtype], device="cuda")
+    M.mtnlg_attention_bwd(b, s, n, d, scale, dev(qkv), a, lse, dev(da), dqkv, ws)
+    o_dqkv = oracle.attention_bwd(dims, to_np(qkv), to_np(da))
+    assert_close(dqkv, o_dqkv, tol * (1.0 if dtype == "fp32" else 1.5), "attention dqkv")
+    got = to_np(dqkv).reshape(b, s, n, 3, d)
+    want = o_dqkv.reshape(b, s, n, 3, d)
+    for i, nm in enumerate("qkv"):
+        assert rel_fro(got[:, :, :, i], want[:, :, :, i]) <= tol * 1.5, f"d{nm}"
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gelu_colsum_bias_residual(dtype):
+    tol = TOL[dtype]
+    z = randn((70, 264), dtype, 30, 2.0)
+    dg = randn((70, 264), dtype, 31)
+    for form, exact in ((B.GELU_TANH, False), (B.GELU_ERF, True)):
+        g = torch.empty(z.shape, dtype=DT[dtype], device="cuda")
+        M.mtnlg_gelu_fwd(dev(z), g, gelu=form)
+        assert_close(g, oracle.gelu(to_np(z), exact), tol, "gelu")
+        dz = torch.empty_like(g)
+        M.mtnlg_gelu_bwd(dev(z), dev(dg), dz, gelu=form)
+        assert_close(dz, to_np(dg) * oracle.gelu_grad(to_np(z), exact), tol, "gelu bwd")
+    for T, C in ((70, 264), (1, 8), (3000, 520), (257, 10240)):
+        x = randn((T, C), dtype, 32)
+        ws = torch.empty(M.mtnlg_colsum_workspace(T, C), dtype=torch.uint8, device="cuda")
+        for odt in (torch.float32, DT[dtype]):
+            out = torch.full((C,), float("nan"), dtype=odt, device="cuda")
+            M.mtnlg_colsum(dev(x), out, ws)
+            assert_close(out, to_np(x).sum(0), tol, f"colsum {T}x{C}")
+            M.mtnlg_colsum(dev(x), out, ws, accumulate=True)
+            assert_close(out, 2 * to_np(x).sum(0), tol * 1.5, "colsum accumulate")
+    res, part, bias = randn((70, 264), dtype, 33), randn((70, 264), dtype, 34), randn((264,), dtype, 35)
+    out = torch.empty((70, 264), dtype=DT[dtype], device="cuda")
+    M.mtnlg_bias_residual(dev(res), dev(part), dev(bias), out)
+    assert_close(out, to_np(res) + to_np(part) + to_np(bias), tol, "bias_residual")
+    M.mtnlg_bias_residual(dev(res), dev(part), None, out)
+    assert_close(out, to_np(res) + to_np(part), tol, "residual")
