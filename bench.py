@@ -1,0 +1,145 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: mtnlg_stage_step (forward + backward of one GPU's
+tensor-parallel slice of a 3-layer pipeline stage) at MT-NLG's per-GPU shapes.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Prints ONE JSON line.  `value` is model TFLOP/s of the whole step (3x forward, attention counted on
+the causal half), inputs resident in HBM.  `roofline` is for the dominant kernel class (the bf16 MFMA
+GEMMs), timed live with HIP events on the launch stream during the timed steps.  `cpu_baseline` is the
+fp64 oracle timed on the host cores on a bounded sample (a causal prefix of one layer).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+
+def gemm_flops_per_step(wl):
+    """FLOPs of one stage step that run in each GEMM kernel class (forward NT, dgrad NN, wgrad TN)."""
+    T, h, p, F = wl.tokens, wl.hidden, wl.proj, wl.ffn
+    per_layer = 2 * T * (h * 3 * p + p * h + h * F + F * h)
+    fwd_passes = 2 if wl.recompute else 1  # a recomputed forward reruns QKV, proj, FC1 (not FC2)
+    nt = per_layer + (fwd_passes - 1) * (per_layer - 2 * T * F * h) * (wl.n_layers - 1) / wl.n_layers
+    return {"gemm_nt": wl.n_layers * nt, "gemm_nn": wl.n_layers * per_layer, "gemm_tn": wl.n_layers * per_layer}
+
+
+def cpu_baseline(wl, weights0, x, prefix):
+    """Time the oracle (as it stands) on layer 0 restricted to the first `prefix` tokens: by causality
+    that is exactly the `prefix`-token problem with the full-width weights."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2201_11990_amd import flops
+
+    dims = oracle.Dims(wl.hidden, wl.heads, wl.head_dim, wl.ffn, prefix, wl.micro_batch)
+    w = {k: v.detach().to("cpu", torch.float64).numpy() for k, v in weights0.items()}
+    xs = x[:, :prefix].detach().to("cpu", torch.float64).numpy().reshape(-1, wl.hidden)
+    dy = np.random.default_rng(0).standard_normal(xs.shape)
+    t0 = time.perf_counter()
+    _, saved = oracle.layer_fwd(dims, w, xs)
+    oracle.layer_bwd(dims, w, xs, saved, dy)
+    dt = time.perf_counter() - t0
+    fl = 3 * flops.layer_forward_flops(wl.hidden, wl.heads, wl.head_dim, wl.ffn, prefix, wl.micro_batch)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle, layer 0 fwd+bwd on the first {prefix} tokens (causal prefix, full-width "
+                      f"weights), {fl / 1e9:.1f} GFLOP in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mtnlg_tp8_stage")
+    ap.add_argument("--cpu-prefix", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2201_11990_amd as M
+    from paper_2201_11990_amd import flops
+    from paper_2201_11990_amd.inputs import WORKLOADS, make_activations, make_layer_params
+    from paper_2201_11990_amd.runner import StageRunner
+
+    wl = WORKLOADS[args.workload]
+    if wl.dtype != "bf16":
+        print("bench.py: benchmark workloads are bf16", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    weights = [make_layer_params(wl, l, seed=0, device=dev) for l in range(wl.n_layers)]
+    x, dy = make_activations(wl, seed=0, device=dev)
+    run = StageRunner(wl, weights, device=dev)
+
+    for _ in range(args.warmup):
+        run.step(x, dy)
+    torch.cuda.synchronize()
+    if not args.no_kernel_timing:
+        M.mtnlg_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run.step(x, dy)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = None
+    if not args.no_kernel_timing:
+        prof = M.mtnlg_profile_read()
+        M.mtnlg_profile_enable(False)
+
+    ms = dt / args.steps * 1e3
+    model = flops.step_model_flops(wl, "causal")
+    value = model / (ms * 1e-3) / 1e12
+    out = {
+        "metric": "model TFLOP/s per GPU, MT-NLG TP=8-slice layer fwd+bwd; % of bf16 MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "hidden": wl.hidden, "heads_local": wl.heads, "head_dim": wl.head_dim,
+                   "ffn_local": wl.ffn, "seq": wl.seq, "micro_batch": wl.micro_batch, "n_layers": wl.n_layers,
+                   "tp_size": wl.tp_size, "recompute": wl.recompute, "parallelism": "one GPU's TP slice, no collectives"},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "model_tflops_paper_convention": round(flops.step_model_flops(wl, "full") / (ms * 1e-3) / 1e12, 2),
+        "hardware_tflops": round(flops.step_hardware_flops(wl, "causal") / (ms * 1e-3) / 1e12, 2),
+    }
+    if prof is not None:
+        gf = gemm_flops_per_step(wl)
+        classes = {}
+        for k, (n, tms) in prof.items():
+            if n:
+                classes[k] = {"launches_per_step": n / args.steps, "ms_per_step": round(tms / args.steps, 4)}
+        dom = max(("gemm_nt", "gemm_nn", "gemm_tn"), key=lambda k: prof[k][1])
+        g_ms = sum(prof[k][1] for k in gf) / args.steps
+        for k in gf:
+            classes[k]["tflops"] = round(gf[k] / (prof[k][1] / args.steps * 1e-3) / 1e12, 1)
+        ach = gf[dom] / (prof[dom][1] / args.steps * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS,
+                           "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "all_gemm_tflops": round(sum(gf.values()) / (g_ms * 1e-3) / 1e12, 1),
+                           "gemm_share_of_step": round(g_ms / ms, 3)}
+        out["kernel_classes"] = classes
+    else:
+        out["roofline"] = {"bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": None, "traffic": None}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, weights[0], x, args.cpu_prefix)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -297,6 +297,11 @@ def attn_half_bwd(dims, w, saved, dA):
     return du, {k: grads[k] for k in ("w_o", "w_qkv", "b_qkv")}
 
 
+def num_threads():
+    """OpenMP threads the oracle's loops use."""
+    return int(lib().orc_num_threads())
+
+
 def stage_step(dims, weights, x, dy):
     """n_layers slices stacked (identity at the reduce points): forward through all
     layers, backward in reverse.  Returns (y, dx, [grads per layer])."""

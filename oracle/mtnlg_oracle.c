@@ -35,6 +35,7 @@
  * and the paper's closed forms (parameter count, activation bytes, init std).
  */
 #include <math.h>
+#include <omp.h>
 #include <stddef.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -429,3 +430,6 @@ void orc_layer_bwd(const orc_dims *D, const orc_weights *W, const double *x,
 }
 
 int orc_abi_version(void) { return 1; }
+
+/* Threads the parallel loops above will use (for reporting next to timings). */
+int orc_num_threads(void) { return omp_get_max_threads(); }

@@ -80,6 +80,32 @@ __device__ __forceinline__ float gelu_grad_f(float z, bool erf_form) {
   return 0.5f * (1.0f + th) + 0.5f * z * (1.0f - th * th) * dinner;
 }
 
+// GEMM epilogue shared by the GEMM kernels: bias, GeLU (pre-activation kept in aux),
+// residual from aux, accumulate, fp32 or storage-dtype output.  One element at a time.
+struct EpiArgs {
+  const void *bias;
+  void *aux;
+  uint32_t flags;
+};
+
+template <typename E>
+__device__ __forceinline__ void epilogue_store(const EpiArgs &ea, void *C, int64_t ldc, int64_t m,
+                                               int64_t n, float acc) {
+  if (ea.flags & MTNLG_EPI_BIAS) acc += to_f32(static_cast<const E *>(ea.bias)[n]);
+  if (ea.flags & MTNLG_EPI_GELU) {
+    static_cast<E *>(ea.aux)[m * ldc + n] = from_f32<E>(acc);
+    acc = gelu_f(acc, (ea.flags & MTNLG_EPI_GELU_ERF) != 0);
+  }
+  if (ea.flags & MTNLG_EPI_RESIDUAL) acc += to_f32(static_cast<const E *>(ea.aux)[m * ldc + n]);
+  if (ea.flags & MTNLG_EPI_OUT_F32) {
+    float *c = static_cast<float *>(C) + m * ldc + n;
+    *c = (ea.flags & MTNLG_EPI_ACCUMULATE) ? *c + acc : acc;
+  } else {
+    E *c = static_cast<E *>(C) + m * ldc + n;
+    *c = from_f32<E>((ea.flags & MTNLG_EPI_ACCUMULATE) ? to_f32(*c) + acc : acc);
+  }
+}
+
 // ---- host side -------------------------------------------------------------
 // Brackets a launch with HIP events when per-class timing is on (profile.cpp).
 struct LaunchScope {

@@ -7,30 +7,6 @@
 
 namespace mtnlg {
 
-struct EpiArgs {
-  const void *bias;
-  void *aux;
-  uint32_t flags;
-};
-
-template <typename E>
-__device__ __forceinline__ void epilogue_store(const EpiArgs &ea, void *C, int64_t ldc, int64_t m,
-                                               int64_t n, float acc) {
-  if (ea.flags & MTNLG_EPI_BIAS) acc += to_f32(static_cast<const E *>(ea.bias)[n]);
-  if (ea.flags & MTNLG_EPI_GELU) {
-    static_cast<E *>(ea.aux)[m * ldc + n] = from_f32<E>(acc);
-    acc = gelu_f(acc, (ea.flags & MTNLG_EPI_GELU_ERF) != 0);
-  }
-  if (ea.flags & MTNLG_EPI_RESIDUAL) acc += to_f32(static_cast<const E *>(ea.aux)[m * ldc + n]);
-  if (ea.flags & MTNLG_EPI_OUT_F32) {
-    float *c = static_cast<float *>(C) + m * ldc + n;
-    *c = (ea.flags & MTNLG_EPI_ACCUMULATE) ? *c + acc : acc;
-  } else {
-    E *c = static_cast<E *>(C) + m * ldc + n;
-    *c = from_f32<E>((ea.flags & MTNLG_EPI_ACCUMULATE) ? to_f32(*c) + acc : acc);
-  }
-}
-
 constexpr int GT = 64, GK = 16;
 
 template <typename E>
