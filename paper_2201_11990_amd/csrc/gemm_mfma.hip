@@ -12,15 +12,18 @@
 //   c ^ (r & 7) ^ ((r >> 3) & 7), which keeps both kinds of LDS writes and the
 //   MFMA operand reads (32 rows x one chunk per half-wave) free of bank conflicts.
 //
-// Workgroup = 256 threads = 2 x 2 waves; workgroup tile BM x BN, wave tile
-// (BM/2) x (BN/2) built from 32x32 MFMA blocks; K advances 64 at a time through two
-// LDS stages (global loads for tile i+1 are in flight while tile i is multiplied).
+// Workgroup = WGM x WGN waves (256x256 tile on 2 x 4 waves by default, 128x128 on 2 x 2
+// for small problems); wave tile built from 32x32 MFMA blocks; K advances 64 at a time
+// through two LDS stages (global loads for slab i+1 are in flight while slab i is
+// multiplied), with the LDS traffic interleaved between the MFMAs by scheduling hints.
 // Workgroups are numbered so that the 8 XCDs (workgroup id mod 8) each own a
 // contiguous run of column-major tiles: neighbours in an XCD's L2 share B panels.
 //
 // Requirements: K % 8 == 0 and N % 8 == 0; a row-contiguous A also needs M % 8 == 0
 // (16-byte accesses never straddle an edge).  Other edges are handled by clamped
 // loads and masked stores.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace mtnlg {
@@ -46,16 +49,16 @@ typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 // ---- global -> registers -> LDS for one ROWS x 64 operand tile ----------------
-// K-contiguous source: ROWS*8 chunks of 16 B, ROWS/32 per thread.
-template <int ROWS>
+// K-contiguous source: ROWS*8 chunks of 16 B spread over NTHR threads.
+template <int ROWS, int NTHR>
 struct LoadK {
-  static constexpr int N = ROWS / 32;
+  static constexpr int N = ROWS * 8 / NTHR;
   i32x4 r[N];
   template <bool KTAIL>
   __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      int q = threadIdx.x + 256 * i;
+      int q = threadIdx.x + NTHR * i;
       int row = q >> 3, c = q & 7;
       int64_t rr = row < rows_valid ? row : rows_valid - 1;
       int64_t k = k0 + c * 8;
@@ -71,7 +74,7 @@ struct LoadK {
   __device__ __forceinline__ void stash(char *lds) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      int q = threadIdx.x + 256 * i;
+      int q = threadIdx.x + NTHR * i;
       int row = q >> 3, c = q & 7;
       *reinterpret_cast<i32x4 *>(lds + row * 128 + swz(row, c)) = r[i];
     }
@@ -79,14 +82,24 @@ struct LoadK {
 };
 
 // Row-contiguous source ([k][row] in memory): each thread owns KB k-rows x 8 rows.
-template <int ROWS>
+// A wave covers 8 row-blocks x 8 k-blocks, which spreads its transposed LDS writes
+// evenly over the banks.
+template <int ROWS, int NTHR>
 struct LoadT {
-  static constexpr int KB = ROWS / 32;  // 8 for 256 rows, 4 for 128
-  static constexpr int RB = ROWS / 8;   // row blocks
+  static constexpr int KB = ROWS * 8 / NTHR;  // k-rows per thread: 8, 4 or 2
+  static constexpr int RBH = ROWS / 64;       // groups of 8 row-blocks
   i16x8 r[KB];
+  __device__ __forceinline__ static int row_block() {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    return (wave % RBH) * 8 + (lane & 7);
+  }
+  __device__ __forceinline__ static int k_block() {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    return (wave / RBH) * 8 + (lane >> 3);
+  }
   template <bool KTAIL>
   __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K) {
-    const int rb = threadIdx.x % RB, kb = threadIdx.x / RB;
+    const int rb = row_block(), kb = k_block();
     int64_t row = rb * 8;
     if (row + 8 > rows_valid) row = rows_valid - 8;  // rows_valid >= 8 and a multiple of 8
 #pragma unroll
@@ -102,55 +115,75 @@ struct LoadT {
     }
   }
   __device__ __forceinline__ void stash(char *lds) const {
-    const int rb = threadIdx.x % RB, kb = threadIdx.x / RB;
+    const int rb = row_block(), kb = k_block();
+    const int chunk = (kb * KB) >> 3, off = ((kb * KB) & 7) * 2;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = rb * 8 + i;
-      if constexpr (KB == 8) {
-        i16x8 t;
+      typedef __attribute__((ext_vector_type(KB))) short vec_t;
+      vec_t t;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) t[j] = r[j][i];
-        *reinterpret_cast<i16x8 *>(lds + row * 128 + swz(row, kb)) = t;
-      } else {
-        i16x4 t;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) t[j] = r[j][i];
-        *reinterpret_cast<i16x4 *>(lds + row * 128 + swz(row, kb >> 1) + (kb & 1) * 8) = t;
-      }
+      for (int j = 0; j < KB; ++j) t[j] = r[j][i];
+      *reinterpret_cast<vec_t *>(lds + row * 128 + swz(row, chunk) + off) = t;
     }
   }
 };
 
-template <int ROWS, bool T>
-struct Loader;
-template <int ROWS>
-struct Loader<ROWS, false> : LoadK<ROWS> {};
-template <int ROWS>
-struct Loader<ROWS, true> : LoadT<ROWS> {};
+// Scheduling hints: REP times {NA instructions of class MASK_A, then NB of class MASK_B}.
+constexpr int SCHED_MFMA = 0x008, SCHED_DS_READ = 0x100, SCHED_DS_WRITE = 0x200;
+template <int MASK_A, int NA, int MASK_B, int NB, int REP>
+__device__ __forceinline__ void sched_pairs() {
+  if constexpr (REP > 0) {
+    __builtin_amdgcn_sched_group_barrier(MASK_A, NA, 0);
+    __builtin_amdgcn_sched_group_barrier(MASK_B, NB, 0);
+    sched_pairs<MASK_A, NA, MASK_B, NB, REP - 1>();
+  }
+}
 
-// KTAIL: K is not a multiple of 64, so the last K-slab is partly zero-filled.
-template <int BM, int BN, bool AT, bool BT, bool KTAIL>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs g) {
+template <int ROWS, int NTHR, bool T>
+struct Loader;
+template <int ROWS, int NTHR>
+struct Loader<ROWS, NTHR, false> : LoadK<ROWS, NTHR> {};
+template <int ROWS, int NTHR>
+struct Loader<ROWS, NTHR, true> : LoadT<ROWS, NTHR> {};
+
+// Tile order: tiles are numbered so that 32 consecutive ids form an 8 (m) x 4 (n)
+// block; XCD x (workgroup id mod 8) owns ids [x*per_xcd, (x+1)*per_xcd), so the
+// workgroups resident on one XCD at a time share A and B panels in its L2.
+__device__ __forceinline__ void tile_coords(const GemmArgs &g, int pid, int &tm, int &tn) {
+  constexpr int GM = 8;
+  const int per_group = GM * g.tiles_n;
+  const int group = pid / per_group, first_m = group * GM;
+  const int gsz = g.tiles_m - first_m < GM ? g.tiles_m - first_m : GM;
+  tm = first_m + (pid % per_group) % gsz;
+  tn = (pid % per_group) / gsz;
+}
+
+// WGM x WGN waves per workgroup.  KTAIL: K is not a multiple of 64, so the last
+// K-slab is partly zero-filled.
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, bool KTAIL>
+__global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int NTHR = 64 * WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
 
-  // XCD-aware tile numbering
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int tile = xcd * g.per_xcd + local;
-  if (local >= g.per_xcd || tile >= g.tiles_m * g.tiles_n) return;
-  const int tm = tile % g.tiles_m, tn = tile / g.tiles_m;
+  const int pid = xcd * g.per_xcd + local;
+  if (local >= g.per_xcd || pid >= g.tiles_m * g.tiles_n) return;
+  int tm, tn;
+  tile_coords(g, pid, tm, tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   const bf16 *Abase = AT ? g.A + m0 : g.A + m0 * g.lda;
   const bf16 *Bbase = BT ? g.B + n0 : g.B + n0 * g.ldb;
   const int64_t a_rows = g.M - m0, b_rows = g.N - n0;
 
-  Loader<BM, AT> la;
-  Loader<BN, BT> lb;
+  Loader<BM, NTHR, AT> la;
+  Loader<BN, NTHR, BT> lb;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -160,57 +193,86 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // per-lane fragment addressing: row (lane & 31) of a 32-row block, chunk 2*kk + (lane >> 5)
+  const int frow = lane & 31, fchunk = lane >> 5;
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto read_frags = [&](const char *buf, int kk, bf16x8(&fa)[TM], bf16x8(&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int row = wm * WM + i * 32 + frow;
+      fa[i] = *reinterpret_cast<const bf16x8 *>(buf + row * 128 + swz(row, kk * 2 + fchunk));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      int row = wn * WN + j * 32 + frow;
+      fb[j] = *reinterpret_cast<const bf16x8 *>(buf + A_BYTES + row * 128 + swz(row, kk * 2 + fchunk));
+    }
+  };
+
   const int nk = (int)((g.K + BK - 1) / BK);
   la.template fetch<KTAIL>(Abase, g.lda, a_rows, 0, g.K);
   lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, 0, g.K);
   la.stash(smem);
   lb.stash(smem + A_BYTES);
   __syncthreads();
+  read_frags(smem, 0, af[0], bfr[0]);
 
-  // per-lane fragment addressing: row (lane & 31) of a 32-row block, chunk 2*kk + (lane >> 5)
-  const int frow = lane & 31, fchunk = lane >> 5;
+  // Software pipeline, pinned with scheduling barriers so that the compiler keeps it:
+  //   top      : global loads of slab it+1 (16-byte, into registers)
+  //   k-step kk: the LDS reads of k-step kk+1 are interleaved with the MFMAs of kk
+  //   last step: first half of its MFMAs interleaved with the LDS writes of the new
+  //              slab, workgroup barrier, then the first fragment reads of the new
+  //              slab are issued under the second half of the MFMAs.
+  // The final iteration reloads the last slab instead of branching; nobody reads it.
+  constexpr int NM = TM * TN, NR = TM + TN;
+  constexpr int NW = (AT ? 8 : BM * 8 / NTHR) + (BT ? 8 : BN * 8 / NTHR);  // LDS writes per slab
+  auto mfma_rows = [&](int buf, int i_begin, int i_end) {
+#pragma unroll
+    for (int i = i_begin; i < i_end; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+  };
   for (int it = 0; it < nk; ++it) {
-    char *cur = smem + (it & 1) * STAGE;
+    const char *cur = smem + (it & 1) * STAGE;
     char *nxt = smem + ((it + 1) & 1) * STAGE;
-    const bool more = it + 1 < nk;
-    if (more) {
-      la.template fetch<KTAIL>(Abase, g.lda, a_rows, (int64_t)(it + 1) * BK, g.K);
-      lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, (int64_t)(it + 1) * BK, g.K);
-    }
+    const int64_t k_next = (int64_t)(it + 1 < nk ? it + 1 : it) * BK;
+    la.template fetch<KTAIL>(Abase, g.lda, a_rows, k_next, g.K);
+    lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, k_next, g.K);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        int row = wm * WM + i * 32 + frow;
-        af[i] = *reinterpret_cast<const bf16x8 *>(cur + row * 128 + swz(row, kk * 2 + fchunk));
+    for (int kk = 0; kk < KS - 1; ++kk) {
+      read_frags(cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+      mfma_rows(kk & 1, 0, TM);
+      if constexpr (NM % NR == 0) {
+        sched_pairs<SCHED_DS_READ, 1, SCHED_MFMA, NM / NR, NR>();
+      } else {  // 6 reads, 8 MFMAs
+        sched_pairs<SCHED_DS_READ, 1, SCHED_MFMA, 1, NR - (NM - NR)>();
+        sched_pairs<SCHED_DS_READ, 1, SCHED_MFMA, 2, NM - NR>();
       }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        int row = wn * WN + j * 32 + frow;
-        bfr[j] = *reinterpret_cast<const bf16x8 *>(cur + A_BYTES + row * 128 + swz(row, kk * 2 + fchunk));
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) {
-      la.stash(nxt);
-      lb.stash(nxt + A_BYTES);
-    }
+    la.stash(nxt);
+    lb.stash(nxt + A_BYTES);
+    mfma_rows((KS - 1) & 1, 0, TM / 2);
+    sched_pairs<SCHED_MFMA, 1, SCHED_DS_WRITE, NW / (NM / 2), NM / 2>();
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(nxt, 0, af[0], bfr[0]);
+    mfma_rows((KS - 1) & 1, TM / 2, TM);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  __syncthreads();
 
-  // Epilogue through LDS, one half (wm) of the tile at a time: accumulators are
-  // written as a [BM/2][BN] fp32 image (element e of lane l is row 8*(e/4) + 4*(l/32)
+  // Epilogue through LDS, one wave-row (wm) of the tile at a time: accumulators are
+  // written as a [WM][BN] fp32 image (element e of lane l is row 8*(e/4) + 4*(l/32)
   // + e%4, column l%32 of its 32x32 block), then every thread walks the image in
   // 8-element row segments and applies bias / GeLU / residual / accumulate with
   // 16-byte global accesses.
   float *img = reinterpret_cast<float *>(smem);
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
+  for (int half = 0; half < WGM; ++half) {
     if (wm == half) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -225,9 +287,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs g) {
     }
     __syncthreads();
     const uint32_t flags = g.ea.flags;
-    for (int idx = threadIdx.x; idx < (BM / 2) * (BN / 8); idx += 256) {
+    for (int idx = threadIdx.x; idx < WM * (BN / 8); idx += NTHR) {
       const int row = idx / (BN / 8), cv = idx % (BN / 8);
-      const int64_t m = m0 + half * (BM / 2) + row, n = n0 + cv * 8;
+      const int64_t m = m0 + half * WM + row, n = n0 + cv * 8;
       if (m >= g.M || n >= g.N) continue;
       float v[8], t[8];
       const f32x4 lo = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8);
@@ -273,7 +335,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, bool AT, bool BT, bool KTAIL>
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, bool KTAIL>
 int launch_k(const GemmArgs &in, hipStream_t st) {
   GemmArgs g = in;
   g.tiles_m = (int)((g.M + BM - 1) / BM);
@@ -281,35 +343,53 @@ int launch_k(const GemmArgs &in, hipStream_t st) {
   const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
   if (tiles > (1 << 28)) return MTNLG_UNSUPPORTED_SHAPE;
   g.per_xcd = (int)((tiles + 7) / 8);
-  constexpr int smem = 2 * (BM + BN) * BK * 2;
+  constexpr int stages = 2 * (BM + BN) * BK * 2, image = (BM / WGM) * BN * 4;
+  constexpr int smem = stages > image ? stages : image;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void *)gemm_bf16_kernel<BM, BN, AT, BT, KTAIL>,
+    if (hipFuncSetAttribute((const void *)gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return MTNLG_HIP_ERROR;
     attr_set = true;
   }
-  gemm_bf16_kernel<BM, BN, AT, BT, KTAIL><<<dim3((unsigned)(g.per_xcd * 8)), 256, smem, st>>>(g);
+  gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL>
+      <<<dim3((unsigned)(g.per_xcd * 8)), 64 * WGM * WGN, smem, st>>>(g);
   return check_launch();
 }
 
-template <int BM, int BN, bool AT, bool BT>
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT>
 int launch(const GemmArgs &g, hipStream_t st) {
-  return g.K % BK ? launch_k<BM, BN, AT, BT, true>(g, st) : launch_k<BM, BN, AT, BT, false>(g, st);
+  return g.K % BK ? launch_k<BM, BN, WGM, WGN, AT, BT, true>(g, st)
+                  : launch_k<BM, BN, WGM, WGN, AT, BT, false>(g, st);
+}
+
+// Tile shapes on offer: {BM, BN, waves_m, waves_n}
+enum TileConfig { T256x256_2x2 = 0, T128x128_2x2, T256x256_2x4, T256x128_2x2, T128x256_2x2, TILE_CONFIGS };
+
+template <bool AT, bool BT>
+int launch_config(int cfg, const GemmArgs &g, hipStream_t st) {
+  switch (cfg) {
+    case T256x256_2x2: return launch<256, 256, 2, 2, AT, BT>(g, st);
+    case T128x128_2x2: return launch<128, 128, 2, 2, AT, BT>(g, st);
+    case T256x256_2x4: return launch<256, 256, 2, 4, AT, BT>(g, st);
+    case T256x128_2x2: return launch<256, 128, 2, 2, AT, BT>(g, st);
+    case T128x256_2x2: return launch<128, 256, 2, 2, AT, BT>(g, st);
+    default: return MTNLG_INVALID_ARG;
+  }
 }
 
 template <bool AT, bool BT>
 int pick_tile(const GemmArgs &g, hipStream_t st) {
-  // Few large tiles when the problem fills the chip several times over, smaller ones
-  // otherwise so that the last round of workgroups is not mostly idle.
-  auto rounds_eff = [&](int bm, int bn) {
-    double tiles = (double)((g.M + bm - 1) / bm) * (double)((g.N + bn - 1) / bn);
-    double rounds = ceil(tiles / 256.0);
-    return tiles / (rounds * 256.0);
-  };
-  const double e256 = rounds_eff(256, 256), e128 = rounds_eff(128, 128) * 0.85;
-  if (e256 >= e128) return launch<256, 256, AT, BT>(g, st);
-  return launch<128, 128, AT, BT>(g, st);
+  // MTNLG_GEMM_TILE=<0..4> forces one tile shape (tuning aid).
+  static const int forced = [] {
+    const char *e = getenv("MTNLG_GEMM_TILE");
+    return e ? atoi(e) : -1;
+  }();
+  if (forced >= 0 && forced < TILE_CONFIGS) return launch_config<AT, BT>(forced, g, st);
+  // 256x256 tiles on 8 waves measure fastest per tile; problems too small to give
+  // most of the 256 CUs one such tile take 128x128 tiles (two workgroups per CU).
+  const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+  return launch_config<AT, BT>(tiles256 < 160 ? T128x128_2x2 : T256x256_2x4, g, st);
 }
 
 }  // namespace
