@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--workload", default="mtnlg_tp8_stage")
     ap.add_argument("--cpu-prefix", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="before the timed steps, run one plain device copy of BYTES (a known-size kernel to "
+                         "calibrate FETCH_SIZE / WRITE_SIZE counters against)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
     args = ap.parse_args()
@@ -89,6 +92,12 @@ def main():
     for _ in range(args.warmup):
         run.step(x, dy)
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_kernel_timing:
         M.mtnlg_profile_enable(True)
     torch.cuda.synchronize()

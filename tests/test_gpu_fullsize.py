@@ -1,0 +1,188 @@
+"""Parity at the benchmark's full sizes (MT-NLG per-GPU slice: h 20480, 16 heads x 160, FFN 10240,
+seq 2048), in the launch configuration bench.py times.
+
+The fp64 oracle cannot run the full problem in seconds, so:
+* the whole layer is checked on a causal prefix: with the upstream gradient zero beyond the first n0
+  tokens, rows < n0 of y, all of dx and every weight gradient equal the n0-token problem with the
+  full-width weights (causality), which the oracle computes exactly;
+* every kernel is checked at its full launch shape on sampled outputs the oracle computes one by one
+  from the GPU's own inputs (rows and columns chosen to fall in first / interior / last tiles);
+* the 3-layer stage step is checked for determinism and against chained single-layer calls.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2201_11990_amd as M
+from paper_2201_11990_amd import binding as B
+from paper_2201_11990_amd.inputs import PARAM_NAMES, WORKLOADS, make_activations, make_layer_params
+from paper_2201_11990_amd.runner import LayerRunner, StageRunner
+from parity import TOL, assert_close, oracle_dims, rel_fro, to_np
+
+pytestmark = pytest.mark.gpu
+
+WL = WORKLOADS["mtnlg_tp8_stage"]
+ROWS = [0, 31, 32, 255, 256, 1023, 1500, 2047]
+
+
+def test_slice_layer_on_a_causal_prefix():
+    wl = WL.with_(n_layers=1)
+    n0 = 48
+    w = make_layer_params(wl, 0, seed=0, device="cuda", affine="random")
+    x, dy = make_activations(wl, seed=0, device="cuda")
+    dy[:, n0:] = 0
+    run = LayerRunner(wl, w)
+    y = run.forward(x)
+    dx, grads = run.backward(x, dy)
+    torch.cuda.synchronize()
+    small = oracle_dims(wl.with_(seq=n0))
+    wn = {k: to_np(v) for k, v in w.items()}
+    xs, dys = to_np(x[:, :n0]).reshape(n0, -1), to_np(dy[:, :n0]).reshape(n0, -1)
+    y_o, saved = oracle.layer_fwd(small, wn, xs)
+    dx_o, g_o = oracle.layer_bwd(small, wn, xs, saved, dys)
+    tol = TOL["bf16"]
+    assert_close(y[:, :n0], y_o, tol, "y[:n0]")
+    assert_close(dx[:, :n0], dx_o, tol, "dx[:n0]")
+    assert (dx[:, n0:] == 0).all(), "tokens after the prefix must get exactly zero gradient"
+    for name in PARAM_NAMES:
+        assert_close(grads[name], g_o[name], tol, f"grad {name}")
+
+
+def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    a_shape = (Mm, K) if layout != B.GEMM_TN else (K, Mm)
+    b_shape = (N, K) if layout == B.GEMM_NT else (K, N)
+    A = torch.randn(a_shape, generator=g, device="cuda").bfloat16()
+    Bm = (torch.randn(b_shape, generator=g, device="cuda") * 0.05).bfloat16()
+    bias = torch.randn((N,), generator=g, device="cuda").bfloat16() if epi & B.EPI_BIAS else None
+    aux = torch.randn((Mm, N), generator=g, device="cuda").bfloat16() if epi & (B.EPI_RESIDUAL | B.EPI_GELU) else None
+    C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    res = aux.clone() if epi & B.EPI_RESIDUAL else None
+    M.mtnlg_gemm(layout, A, Bm, C, bias=bias, aux=aux, epilogue=epi)
+    rows = sorted({r for r in (0, 1, 127, 128, 255, 256, Mm // 2 + 3, Mm - 129, Mm - 1)})
+    cols = sorted({c for c in (0, 7, 255, 256, N // 2 + 5, N - 257, N - 1)})
+    An, Bn = to_np(A), to_np(Bm)
+    if layout == B.GEMM_NT:
+        want = oracle.linear_fwd(An[rows], Bn[cols], to_np(bias)[cols] if bias is not None else None)
+    elif layout == B.GEMM_NN:
+        want = oracle.linear_dgrad(An[rows], Bn[:, cols])
+    else:
+        want = oracle.linear_wgrad(An[:, rows], Bn[:, cols])[0]
+    if epi & B.EPI_GELU:
+        assert_close(aux[rows][:, cols], want, TOL["bf16"], "pre-activation samples")
+        want = oracle.gelu(want)
+    if epi & B.EPI_RESIDUAL:
+        want = want + to_np(res)[np.ix_(rows, cols)]
+    assert_close(C[rows][:, cols], want, TOL["bf16"], f"gemm {layout} {Mm}x{N}x{K} samples")
+    assert torch.isfinite(C.float()).all()
+
+
+T, H, P, F = WL.tokens, WL.hidden, WL.proj, WL.ffn
+FULL_GEMMS = [
+    ("qkv", B.GEMM_NT, T, 3 * P, H, B.EPI_BIAS), ("proj", B.GEMM_NT, T, H, P, B.EPI_BIAS | B.EPI_RESIDUAL),
+    ("fc1", B.GEMM_NT, T, F, H, B.EPI_BIAS | B.EPI_GELU), ("fc2", B.GEMM_NT, T, H, F, B.EPI_BIAS | B.EPI_RESIDUAL),
+    ("dfc2", B.GEMM_NN, T, F, H, 0), ("dfc1", B.GEMM_NN, T, H, F, 0), ("dproj", B.GEMM_NN, T, P, H, 0),
+    ("dqkv", B.GEMM_NN, T, H, 3 * P, 0),
+    ("wfc2", B.GEMM_TN, H, F, T, 0), ("wfc1", B.GEMM_TN, F, H, T, 0), ("wproj", B.GEMM_TN, H, P, T, 0),
+    ("wqkv", B.GEMM_TN, 3 * P, H, T, 0),
+]
+
+
+@pytest.mark.parametrize("name,layout,Mm,N,K,epi", FULL_GEMMS, ids=[g[0] for g in FULL_GEMMS])
+def test_gemm_at_full_launch_shape_on_sampled_outputs(name, layout, Mm, N, K, epi):
+    _gemm_case(layout, Mm, N, K, epi, seed=sum(map(ord, name)))
+
+
+def test_attention_at_full_sequence_length_on_sampled_heads():
+    b, s, n, d = WL.micro_batch, WL.seq, WL.heads, WL.head_dim
+    g = torch.Generator(device="cuda").manual_seed(5)
+    qkv = torch.randn((b * s, 3 * n * d), generator=g, device="cuda").bfloat16()
+    da = torch.randn((b * s, n * d), generator=g, device="cuda").bfloat16()
+    a = torch.full((b * s, n * d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((b, n, s), device="cuda")
+    scale = 1 / math.sqrt(d)
+    M.mtnlg_attention_fwd(b, s, n, d, scale, qkv, a, lse)
+    ws = torch.empty(M.mtnlg_attention_bwd_workspace(b, s, n, d), dtype=torch.uint8, device="cuda")
+    dqkv = torch.full(qkv.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_attention_bwd(b, s, n, d, scale, qkv, a, lse, da, dqkv, ws)
+    assert torch.isfinite(a.float()).all() and torch.isfinite(dqkv.float()).all()
+    one = oracle.Dims(hidden=8, heads=1, head_dim=d, ffn=8, seq=s, batch=b)
+    for head in (0, 11):
+        q1 = to_np(qkv[:, head * 3 * d:(head + 1) * 3 * d])
+        da1 = to_np(da[:, head * d:(head + 1) * d])
+        assert_close(a[:, head * d:(head + 1) * d], oracle.attention_fwd(one, q1), TOL["bf16"], f"head {head} out")
+        want = oracle.attention_bwd(one, q1, da1)
+        got = dqkv[:, head * 3 * d:(head + 1) * 3 * d]
+        for i, nm in enumerate("qkv"):
+            assert_close(got[:, i * d:(i + 1) * d], want[:, i * d:(i + 1) * d], 1.5 * TOL["bf16"], f"head {head} d{nm}")
+
+
+def test_rowwise_kernels_at_full_width_on_sampled_rows():
+    g = torch.Generator(device="cuda").manual_seed(6)
+    x = (torch.randn((T, H), generator=g, device="cuda") * 1.5 + 0.2).bfloat16()
+    gamma = (1 + 0.1 * torch.randn((H,), generator=g, device="cuda")).bfloat16()
+    beta = (0.1 * torch.randn((H,), generator=g, device="cuda")).bfloat16()
+    dout = torch.randn((T, H), generator=g, device="cuda").bfloat16()
+    out = torch.empty_like(x)
+    mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
+    M.mtnlg_layernorm_fwd(x, gamma, beta, 1e-5, out, mean, rstd)
+    o_out, o_mean, o_rstd = oracle.layernorm_fwd(to_np(x[ROWS]), to_np(gamma), to_np(beta), 1e-5)
+    assert_close(out[ROWS], o_out, TOL["bf16"], "ln rows")
+    assert_close(mean[ROWS], o_mean, 1e-5, "ln mean")
+    ws = torch.empty(M.mtnlg_layernorm_bwd_workspace(T, H), dtype=torch.uint8, device="cuda")
+    dx = torch.empty_like(x)
+    dgm, dbt, cs = (torch.empty(H, device="cuda") for _ in range(3))
+    M.mtnlg_layernorm_bwd(x, gamma, mean, rstd, dout, dx, dgm, dbt, ws, colsum_dx=cs, grad_f32=True)
+    o_dx, _, _ = oracle.layernorm_bwd(to_np(x[ROWS]), to_np(gamma), to_np(mean[ROWS]), to_np(rstd[ROWS]), to_np(dout[ROWS]))
+    assert_close(dx[ROWS], o_dx, TOL["bf16"], "ln bwd rows")
+    cols = [0, 7, 511, 512, 10000, H - 1]
+    xhat = (to_np(x[:, cols]) - to_np(mean)[:, None]) * to_np(rstd)[:, None]
+    assert_close(dgm[cols], (to_np(dout[:, cols]) * xhat).sum(0), TOL["bf16"], "dgamma cols")
+    assert_close(dbt[cols], to_np(dout[:, cols]).sum(0), TOL["bf16"], "dbeta cols")
+    assert_close(cs[cols], to_np(dx[:, cols]).sum(0), TOL["bf16"], "colsum(dx) cols")
+    z = torch.randn((T, F), generator=g, device="cuda").bfloat16()
+    dz = torch.empty_like(z)
+    M.mtnlg_gelu_bwd(z, dout[:, :F].contiguous(), dz)
+    assert_close(dz[ROWS], to_np(dout[ROWS][:, :F]) * oracle.gelu_grad(to_np(z[ROWS])), TOL["bf16"], "gelu bwd rows")
+
+
+def test_stage_step_in_the_benchmark_configuration_is_deterministic_and_chains_layers():
+    wl = WL
+    ws = [make_layer_params(wl, l, seed=0, device="cuda") for l in range(wl.n_layers)]
+    x, dy = make_activations(wl, seed=0, device="cuda")
+    run = StageRunner(wl, ws)
+    y, dx, grads = run.step(x, dy)
+    y1, dx1 = y.clone(), dx.clone()
+    g1 = [{k: v.clone() for k, v in g.items()} for g in grads]
+    y2, dx2, grads2 = run.step(x, dy)
+    assert torch.isfinite(y2.float()).all() and torch.isfinite(dx2.float()).all()
+    assert torch.equal(y1, y2) and torch.equal(dx1, dx2)
+    for l in range(wl.n_layers):
+        for k in PARAM_NAMES:
+            assert torch.equal(g1[l][k], grads2[l][k]), (l, k)
+            assert torch.isfinite(grads2[l][k].float()).all()
+    del run, grads, grads2
+    # chained single-layer calls give the same bits
+    cur, inputs = x, []
+    runners = []
+    for l in range(wl.n_layers):
+        r = LayerRunner(wl, ws[l])
+        inputs.append(cur)
+        cur = r.forward(cur).clone()
+        runners.append(r)
+    assert torch.equal(cur, y1)
+    gcur = dy
+    for l in reversed(range(wl.n_layers)):
+        d, g = runners[l].backward(inputs[l], gcur)
+        gcur = d.clone()
+        for k in ("w_qkv", "w_fc2", "ln1_g", "b_fc1"):
+            assert torch.equal(g[k], g1[l][k]), (l, k)
+    assert torch.equal(gcur, dx1)
+    # a recomputing step returns the same bits as well
+    rec = StageRunner(wl, ws, flags=B.RECOMPUTE)
+    y3, dx3, g3 = rec.step(x, dy)
+    assert torch.equal(y3, y1) and torch.equal(dx3, dx1)
+    assert all(torch.equal(g3[0][k], g1[0][k]) for k in PARAM_NAMES)
