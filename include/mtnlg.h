@@ -190,9 +190,14 @@ enum mtnlg_gemm_layout {
 
 /* General matrix product with fp32 accumulation, dense row-major operands
  * (leading dimension = row length).  dtype selects float or bf16 inputs.
- * aux: pre-activation output under EPI_GELU, residual input under EPI_RESIDUAL. */
+ * aux: pre-activation output under EPI_GELU, residual input under EPI_RESIDUAL.
+ * workspace (nullable): mtnlg_gemm_workspace() bytes of scratch that lets a problem
+ * whose last round of output tiles would leave most compute units idle split those
+ * tiles along K; without it the same result is computed by whole tiles only. */
+size_t mtnlg_gemm_workspace(int dtype, int layout, int64_t M, int64_t N, int64_t K);
 int mtnlg_gemm(int dtype, int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
-               void *C, const void *bias, void *aux, uint32_t epilogue, void *stream);
+               void *C, const void *bias, void *aux, uint32_t epilogue, void *workspace,
+               size_t workspace_bytes, void *stream);
 
 /* out = LN(x [+ partial + bias]) per token row; if partial != NULL also writes
  * xsum = x + partial + bias (bias may be NULL).  mean/rstd [T] float out. */

@@ -78,7 +78,8 @@ def lib():
             "mtnlg_layer_bwd": (ctypes.c_int, [dp, pp, vp, vp, vp, vp, pp, vp, sz, REDUCE_FN, vp, vp]),
             "mtnlg_stage_step": (ctypes.c_int, [dp, ctypes.c_int, pp, vp, vp, vp, vp, pp, vp, sz, vp, sz,
                                                 REDUCE_FN, vp, vp]),
-            "mtnlg_gemm": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, u32, vp]),
+            "mtnlg_gemm_workspace": (sz, [ctypes.c_int, ctypes.c_int, i64, i64, i64]),
+            "mtnlg_gemm": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, u32, vp, sz, vp]),
             "mtnlg_layernorm_fwd": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]),
             "mtnlg_layernorm_bwd_workspace": (sz, [i64, i64]),
             "mtnlg_layernorm_bwd": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -103,7 +104,7 @@ def lib():
 
 EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "mtnlg_saved_layout_get",
             "mtnlg_saved_bytes", "mtnlg_stage_saved_bytes", "mtnlg_workspace_bytes", "mtnlg_layer_fwd",
-            "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_gemm", "mtnlg_layernorm_fwd",
+            "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
             "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_profile_enable",
@@ -244,7 +245,11 @@ def mtnlg_stage_step(desc, weights, x_in, dy_out, y_out, dx_in, grads, saved, wo
                                   _nbytes(workspace), hook, None, _stream()), "mtnlg_stage_step")
 
 
-def mtnlg_gemm(layout, A, B, C, bias=None, aux=None, epilogue=0):
+def mtnlg_gemm_workspace(dtype, layout, M, N, K):
+    return lib().mtnlg_gemm_workspace(dtype, layout, M, N, K)
+
+
+def mtnlg_gemm(layout, A, B, C, bias=None, aux=None, epilogue=0, workspace=None):
     if layout == GEMM_NT:
         (M, K), N = A.shape, B.shape[0]
         assert B.shape == (N, K)
@@ -256,7 +261,8 @@ def mtnlg_gemm(layout, A, B, C, bias=None, aux=None, epilogue=0):
         assert B.shape == (K, N)
     assert C.shape == (M, N)
     _check(lib().mtnlg_gemm(_dtype_code(A), layout, M, N, K, _p(A), _p(B), _p(C), _p(bias), _p(aux), epilogue,
-                            _stream()), "mtnlg_gemm")
+                            _p(workspace), _nbytes(workspace) if workspace is not None else 0, _stream()),
+           "mtnlg_gemm")
 
 
 def mtnlg_layernorm_fwd(x, gamma, beta, eps, out, mean, rstd, partial=None, bias=None, xsum=None):

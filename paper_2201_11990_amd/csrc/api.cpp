@@ -75,7 +75,7 @@ void saved_layout(const Shape &S, mtnlg_saved_layout *L) {
 
 // Scratch carved from the caller's workspace.
 struct Work {
-  size_t dgz, du, dx1, da, dqkv, red, attn, ping, pong, total;
+  size_t dgz, du, dx1, da, dqkv, red, attn, ping, pong, gemm, gemm_bytes, total;
 };
 
 void work_layout(const Shape &S, Work *W) {
@@ -93,6 +93,17 @@ void work_layout(const Shape &S, Work *W) {
   W->attn = c.take(mtnlg_attention_bwd_workspace(S.b, S.s, S.n, S.d));
   W->ping = c.take(S.T * S.h * S.es);  // stage step: gradient hand-over between layers
   W->pong = c.take(S.T * S.h * S.es);
+  // split-K scratch: the largest need over the layer's twelve GEMMs
+  size_t gw = 0;
+  const int64_t shapes[12][3] = {{S.T, 3 * S.p, S.h}, {S.T, S.h, S.p}, {S.T, S.F, S.h}, {S.T, S.h, S.F},
+                                 {S.T, S.F, S.h}, {S.T, S.h, S.F}, {S.T, S.p, S.h}, {S.T, S.h, 3 * S.p},
+                                 {S.h, S.F, S.T}, {S.F, S.h, S.T}, {S.h, S.p, S.T}, {3 * S.p, S.h, S.T}};
+  for (auto &sh : shapes) {
+    size_t b = mtnlg_gemm_workspace(S.dtype, MTNLG_GEMM_NT, sh[0], sh[1], sh[2]);
+    if (b > gw) gw = b;
+  }
+  W->gemm_bytes = gw;
+  W->gemm = c.take(gw);
   W->total = c.off;
 }
 
@@ -126,7 +137,7 @@ int layer_fwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
   float *mu2 = (float *)at(saved, L.mu2), *rs2 = (float *)at(saved, L.rs2);
   void *u1 = at(saved, L.u1), *qkv = at(saved, L.qkv), *a = at(saved, L.a), *x1 = at(saved, L.x1);
   void *u2 = at(saved, L.u2), *z = at(saved, L.z), *g = at(saved, L.g);
-  void *partial = at(ws, W.du);
+  void *partial = at(ws, W.du), *gws = at(ws, W.gemm);
   const uint32_t gelu_flags = MTNLG_EPI_BIAS | MTNLG_EPI_GELU | (S.gelu_erf ? MTNLG_EPI_GELU_ERF : 0u);
 
   // u1 = LN1(x)
@@ -134,32 +145,32 @@ int layer_fwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
                                 u1, mu1, rs1, st));
   // qkv = u1 Wqkv^T + bqkv
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, 3 * S.p, S.h, u1, w->w_qkv, qkv, w->b_qkv, nullptr,
-                       MTNLG_EPI_BIAS, st));
+                       MTNLG_EPI_BIAS, gws, W.gemm_bytes, st));
   // a = causal attention
   MTNLG_TRY(mtnlg_attention_fwd(S.dtype, S.b, S.s, S.n, S.d, S.scale, qkv, a, (float *)at(saved, L.lse), st));
   if (reduce) {
     // A_r = a Wo^T ; sum over the group ; x1 = x + A + bo ; u2 = LN2(x1)
-    MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.p, a, w->w_o, partial, nullptr, nullptr, 0, st));
+    MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.p, a, w->w_o, partial, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
     MTNLG_TRY(call_reduce(reduce, user, partial, (size_t)(S.T * S.h), S.dtype, st));
     MTNLG_TRY(mtnlg_layernorm_fwd(S.dtype, S.T, S.h, x, partial, w->b_o, w->ln2_g, w->ln2_b, S.eps, x1, u2,
                                   mu2, rs2, st));
   } else {
     // group of one: the residual and bias ride in the projection's epilogue
     MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.p, a, w->w_o, x1, w->b_o, const_cast<void *>(x),
-                         MTNLG_EPI_BIAS | MTNLG_EPI_RESIDUAL, st));
+                         MTNLG_EPI_BIAS | MTNLG_EPI_RESIDUAL, gws, W.gemm_bytes, st));
     MTNLG_TRY(mtnlg_layernorm_fwd(S.dtype, S.T, S.h, x1, nullptr, nullptr, w->ln2_g, w->ln2_b, S.eps, nullptr,
                                   u2, mu2, rs2, st));
   }
   // z = u2 W1^T + b1 ; g = GeLU(z)
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.F, S.h, u2, w->w_fc1, g, w->b_fc1, z, gelu_flags, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.F, S.h, u2, w->w_fc1, g, w->b_fc1, z, gelu_flags, gws, W.gemm_bytes, st));
   if (!with_output) return MTNLG_OK;
   if (reduce) {
-    MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.F, g, w->w_fc2, partial, nullptr, nullptr, 0, st));
+    MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.F, g, w->w_fc2, partial, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
     MTNLG_TRY(call_reduce(reduce, user, partial, (size_t)(S.T * S.h), S.dtype, st));
     MTNLG_TRY(mtnlg_bias_residual(S.dtype, S.T, S.h, x1, partial, w->b_fc2, y, st));
   } else {
     MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NT, S.T, S.h, S.F, g, w->w_fc2, y, w->b_fc2, x1,
-                         MTNLG_EPI_BIAS | MTNLG_EPI_RESIDUAL, st));
+                         MTNLG_EPI_BIAS | MTNLG_EPI_RESIDUAL, gws, W.gemm_bytes, st));
   }
   return MTNLG_OK;
 }
@@ -177,33 +188,33 @@ int layer_bwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
   const void *u2 = at(saved, L.u2), *z = at(saved, L.z), *g = at(saved, L.g);
   const float *lse = (const float *)at(saved, L.lse);
   void *dgz = at(ws, W.dgz), *du = at(ws, W.du), *dx1 = at(ws, W.dx1), *da = at(ws, W.da);
-  void *dqkv = at(ws, W.dqkv), *red = at(ws, W.red), *attn_ws = at(ws, W.attn);
+  void *dqkv = at(ws, W.dqkv), *red = at(ws, W.red), *attn_ws = at(ws, W.attn), *gws = at(ws, W.gemm);
   const int g32 = S.g32 ? 1 : 0, acc = S.acc ? 1 : 0;
   const uint32_t wg_epi = (S.acc ? MTNLG_EPI_ACCUMULATE : 0u) | ((S.g32 && S.dtype == MTNLG_BF16) ? MTNLG_EPI_OUT_F32 : 0u);
 
   // y = x1 + M + b2:  db2 = sum_t dy ; dg = dy W2 ; dW2 = dy^T g
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.h, dy, G->b_fc2, g32, acc, red, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.F, S.h, dy, w->w_fc2, dgz, nullptr, nullptr, 0, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.F, S.T, dy, g, G->w_fc2, nullptr, nullptr, wg_epi, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.F, S.h, dy, w->w_fc2, dgz, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.F, S.T, dy, g, G->w_fc2, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   // dz = dg o GeLU'(z) ; db1 = sum_t dz
   MTNLG_TRY(mtnlg_gelu_bwd(S.dtype, S.gelu_erf, S.T * S.F, z, dgz, dgz, st));
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.F, dgz, G->b_fc1, g32, acc, red, st));
   // du2_r = dz W1 ; dW1 = dz^T u2
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, S.F, dgz, w->w_fc1, du, nullptr, nullptr, 0, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.F, S.h, S.T, dgz, u2, G->w_fc1, nullptr, nullptr, wg_epi, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, S.F, dgz, w->w_fc1, du, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.F, S.h, S.T, dgz, u2, G->w_fc1, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   MTNLG_TRY(call_reduce(reduce, user, du, (size_t)(S.T * S.h), S.dtype, st));
   // dx1 = dy + LN2^T(du2) ; dgamma2, dbeta2 ; dbo = sum_t dx1
   MTNLG_TRY(mtnlg_layernorm_bwd(S.dtype, S.T, S.h, x1, w->ln2_g, mu2, rs2, du, dy, dx1, G->ln2_g, G->ln2_b,
                                 G->b_o, g32, acc, red, st));
   // da = dx1 Wo ; dWo = dx1^T a
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.p, S.h, dx1, w->w_o, da, nullptr, nullptr, 0, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.p, S.T, dx1, a, G->w_o, nullptr, nullptr, wg_epi, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.p, S.h, dx1, w->w_o, da, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.p, S.T, dx1, a, G->w_o, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   // attention backward
   MTNLG_TRY(mtnlg_attention_bwd(S.dtype, S.b, S.s, S.n, S.d, S.scale, qkv, a, lse, da, dqkv, attn_ws, st));
   // dbqkv = sum_t dqkv ; du1_r = dqkv Wqkv ; dWqkv = dqkv^T u1
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, 3 * S.p, dqkv, G->b_qkv, g32, acc, red, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, 3 * S.p, dqkv, w->w_qkv, du, nullptr, nullptr, 0, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, 3 * S.p, S.h, S.T, dqkv, u1, G->w_qkv, nullptr, nullptr, wg_epi, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, 3 * S.p, dqkv, w->w_qkv, du, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, 3 * S.p, S.h, S.T, dqkv, u1, G->w_qkv, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   MTNLG_TRY(call_reduce(reduce, user, du, (size_t)(S.T * S.h), S.dtype, st));
   // dx = dx1 + LN1^T(du1) ; dgamma1, dbeta1
   MTNLG_TRY(mtnlg_layernorm_bwd(S.dtype, S.T, S.h, x, w->ln1_g, mu1, rs1, du, dx1, dx, G->ln1_g, G->ln1_b,
@@ -330,8 +341,14 @@ int mtnlg_stage_step(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_lay
   return MTNLG_OK;
 }
 
+size_t mtnlg_gemm_workspace(int dtype, int layout, int64_t M, int64_t N, int64_t K) {
+  (void)layout;
+  return dtype == MTNLG_BF16 ? gemm_mfma_workspace_bytes(M, N, K) : 0;
+}
+
 int mtnlg_gemm(int dtype, int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
-               const void *bias, void *aux, uint32_t epilogue, void *stream) {
+               const void *bias, void *aux, uint32_t epilogue, void *workspace, size_t workspace_bytes,
+               void *stream) {
   if (!A || !B || !C) return MTNLG_NULL_POINTER;
   if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return MTNLG_INVALID_ARG;
   if (dtype != MTNLG_F32 && dtype != MTNLG_BF16) return MTNLG_INVALID_ARG;
@@ -342,7 +359,7 @@ int mtnlg_gemm(int dtype, int layout, int64_t M, int64_t N, int64_t K, const voi
   if (dtype == MTNLG_F32) epilogue &= ~MTNLG_EPI_OUT_F32;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == MTNLG_BF16) {
-    int r = gemm_mfma_bf16(layout, M, N, K, A, B, C, bias, aux, epilogue, st);
+    int r = gemm_mfma_bf16(layout, M, N, K, A, B, C, bias, aux, epilogue, workspace, workspace_bytes, st);
     if (r != MTNLG_UNSUPPORTED_SHAPE) return r;
   }
   return gemm_generic(dtype, layout, M, N, K, A, B, C, bias, aux, epilogue, st);

@@ -131,8 +131,11 @@ int gemm_generic(int dtype, int layout, int64_t M, int64_t N, int64_t K, const v
                  const void *B, void *C, const void *bias, void *aux, uint32_t epi,
                  hipStream_t stream);
 // returns MTNLG_UNSUPPORTED_SHAPE when the MFMA kernel cannot take this problem
+// ws (nullable): scratch for the split-K tail, see gemm_mfma_workspace_bytes
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
-                   void *C, const void *bias, void *aux, uint32_t epi, hipStream_t stream);
+                   void *C, const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes,
+                   hipStream_t stream);
+size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int attention_fwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
                          void *a, float *lse, hipStream_t stream);
 int attention_bwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,

@@ -40,6 +40,10 @@ struct GemmArgs {
   int64_t ldc;
   EpiArgs ea;
   int tiles_m, tiles_n, per_xcd;
+  // split-K tail: tiles [whole_tiles, tiles) are each computed by `split` workgroups,
+  // `part_slabs` K-slabs apiece, which leave fp32 partial tiles in `partial`
+  int whole_tiles, split, part_slabs;
+  float *partial;
 };
 
 __device__ __forceinline__ int swz(int r, int c) { return (c ^ (r & 7) ^ ((r >> 3) & 7)) << 4; }
@@ -147,6 +151,46 @@ struct Loader<ROWS, NTHR, false> : LoadK<ROWS, NTHR> {};
 template <int ROWS, int NTHR>
 struct Loader<ROWS, NTHR, true> : LoadT<ROWS, NTHR> {};
 
+// Bias / GeLU / residual / accumulate / store for 8 consecutive outputs of row m at column n.
+__device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t n, float (&v)[8]) {
+  const uint32_t flags = g.ea.flags;
+  const int64_t off = m * g.ldc + n;
+  float t[8];
+  if (flags & MTNLG_EPI_BIAS) {
+    load8(static_cast<const bf16 *>(g.ea.bias) + n, t);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += t[e];
+  }
+  if (flags & MTNLG_EPI_GELU) {
+    store8(static_cast<bf16 *>(g.ea.aux) + off, v);
+    const bool erf_form = (flags & MTNLG_EPI_GELU_ERF) != 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e], erf_form);
+  }
+  if (flags & MTNLG_EPI_RESIDUAL) {
+    load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += t[e];
+  }
+  if (flags & MTNLG_EPI_OUT_F32) {
+    float *c = static_cast<float *>(g.C) + off;
+    if (flags & MTNLG_EPI_ACCUMULATE) {
+      load8(c, t);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += t[e];
+    }
+    store8(c, v);
+  } else {
+    bf16 *c = static_cast<bf16 *>(g.C) + off;
+    if (flags & MTNLG_EPI_ACCUMULATE) {
+      load8(c, t);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += t[e];
+    }
+    store8(c, v);
+  }
+}
+
 // Tile order: tiles are numbered so that 32 consecutive ids form an 8 (m) x 4 (n)
 // block; XCD x (workgroup id mod 8) owns ids [x*per_xcd, (x+1)*per_xcd), so the
 // workgroups resident on one XCD at a time share A and B panels in its L2.
@@ -168,9 +212,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
 
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int pid = xcd * g.per_xcd + local;
-  if (local >= g.per_xcd || pid >= g.tiles_m * g.tiles_n) return;
+  // Workgroups [0, 8*per_xcd) take whole tiles (XCD-aware numbering); the rest take
+  // one K-part of a tail tile each.
+  const int nk_all = (int)((g.K + BK - 1) / BK);
+  int pid, slab0 = 0, slab1 = nk_all, part_id = -1;
+  if ((int)blockIdx.x < 8 * g.per_xcd) {
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    pid = xcd * g.per_xcd + local;
+    if (pid >= g.whole_tiles) return;
+  } else {
+    part_id = blockIdx.x - 8 * g.per_xcd;
+    pid = g.whole_tiles + part_id / g.split;
+    slab0 = (part_id % g.split) * g.part_slabs;
+    slab1 = slab0 + g.part_slabs < nk_all ? slab0 + g.part_slabs : nk_all;
+  }
   int tm, tn;
   tile_coords(g, pid, tm, tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
@@ -209,9 +264,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
     }
   };
 
-  const int nk = (int)((g.K + BK - 1) / BK);
-  la.template fetch<KTAIL>(Abase, g.lda, a_rows, 0, g.K);
-  lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, 0, g.K);
+  const int nk = slab1 - slab0;
+  la.template fetch<KTAIL>(Abase, g.lda, a_rows, (int64_t)slab0 * BK, g.K);
+  lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, (int64_t)slab0 * BK, g.K);
   la.stash(smem);
   lb.stash(smem + A_BYTES);
   __syncthreads();
@@ -236,7 +291,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   for (int it = 0; it < nk; ++it) {
     const char *cur = smem + (it & 1) * STAGE;
     char *nxt = smem + ((it + 1) & 1) * STAGE;
-    const int64_t k_next = (int64_t)(it + 1 < nk ? it + 1 : it) * BK;
+    const int64_t k_next = (int64_t)(slab0 + (it + 1 < nk ? it + 1 : it)) * BK;
     la.template fetch<KTAIL>(Abase, g.lda, a_rows, k_next, g.K);
     lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, k_next, g.K);
     __builtin_amdgcn_sched_barrier(0);
@@ -286,63 +341,88 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
           }
     }
     __syncthreads();
-    const uint32_t flags = g.ea.flags;
     for (int idx = threadIdx.x; idx < WM * (BN / 8); idx += NTHR) {
       const int row = idx / (BN / 8), cv = idx % (BN / 8);
-      const int64_t m = m0 + half * WM + row, n = n0 + cv * 8;
-      if (m >= g.M || n >= g.N) continue;
-      float v[8], t[8];
+      float v[8];
       const f32x4 lo = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8);
       const f32x4 hi = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8 + 4);
 #pragma unroll
       for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
-      const int64_t off = m * g.ldc + n;
-      if (flags & MTNLG_EPI_BIAS) {
-        load8(static_cast<const bf16 *>(g.ea.bias) + n, t);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += t[e];
-      }
-      if (flags & MTNLG_EPI_GELU) {
-        store8(static_cast<bf16 *>(g.ea.aux) + off, v);
-        const bool erf_form = (flags & MTNLG_EPI_GELU_ERF) != 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e], erf_form);
-      }
-      if (flags & MTNLG_EPI_RESIDUAL) {
-        load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += t[e];
-      }
-      if (flags & MTNLG_EPI_OUT_F32) {
-        float *c = static_cast<float *>(g.C) + off;
-        if (flags & MTNLG_EPI_ACCUMULATE) {
-          load8(c, t);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += t[e];
-        }
-        store8(c, v);
+      if (part_id >= 0) {  // K-part of a tail tile: raw fp32 partial, summed by splitk_reduce_kernel
+        store8(g.partial + (int64_t)part_id * (BM * BN) + (half * WM + row) * BN + cv * 8, v);
       } else {
-        bf16 *c = static_cast<bf16 *>(g.C) + off;
-        if (flags & MTNLG_EPI_ACCUMULATE) {
-          load8(c, t);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += t[e];
-        }
-        store8(c, v);
+        const int64_t m = m0 + half * WM + row, n = n0 + cv * 8;
+        if (m < g.M && n < g.N) epilogue8(g, m, n, v);
       }
     }
     __syncthreads();
   }
 }
 
+// Sum the `split` fp32 partial tiles of each tail tile in a fixed order and run the epilogue.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g) {
+  const int tail = blockIdx.y;  // tail tile index
+  int tm, tn;
+  tile_coords(g, g.whole_tiles + tail, tm, tn);
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < BM * (BN / 8); idx += gridDim.x * 256) {
+    const int row = idx / (BN / 8), cv = idx % (BN / 8);
+    const int64_t m = m0 + row, n = n0 + cv * 8;
+    if (m >= g.M || n >= g.N) continue;
+    float v[8] = {}, t[8];
+    for (int s = 0; s < g.split; ++s) {
+      load8(g.partial + ((int64_t)tail * g.split + s) * (BM * BN) + row * BN + cv * 8, t);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += t[e];
+    }
+    epilogue8(g, m, n, v);
+  }
+}
+
+// How the tiles of a problem are covered: `whole` tiles by one workgroup each, the
+// remaining tail tiles by `split` workgroups each (split == 1: no tail).
+struct SplitPlan {
+  int whole, tail, split, part_slabs;
+  size_t workspace;
+};
+inline SplitPlan plan_split(int64_t tiles, int nk, int bm, int bn, size_t ws_bytes) {
+  SplitPlan p{(int)tiles, 0, 1, nk, 0};
+  const int cus = 256;
+  const int tail = (int)(tiles % cus);
+  if (tail == 0 || tail > 176) return p;  // the last round is full enough
+  if (tiles >= 4 * cus) return p;          // many rounds: an idle tail costs little, splitting costs more
+  int split = cus / tail;
+  if (split > 8) split = 8;
+  while (split > 1 && nk / split < 8) --split;  // keep K-parts long enough to pipeline
+  while (split > 1 && (split - 1) * ((nk + split - 1) / split) >= nk) --split;  // no empty K-part
+  if (split <= 1) return p;
+  const size_t need = (size_t)tail * split * bm * bn * sizeof(float);
+  p.workspace = need;
+  if (ws_bytes < need) return p;  // caller gave no room: whole tiles only
+  p.whole = (int)(tiles - tail);
+  p.tail = tail;
+  p.split = split;
+  p.part_slabs = (nk + split - 1) / split;
+  return p;
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, bool KTAIL>
-int launch_k(const GemmArgs &in, hipStream_t st) {
+int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
   GemmArgs g = in;
   g.tiles_m = (int)((g.M + BM - 1) / BM);
   g.tiles_n = (int)((g.N + BN - 1) / BN);
   const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
   if (tiles > (1 << 28)) return MTNLG_UNSUPPORTED_SHAPE;
-  g.per_xcd = (int)((tiles + 7) / 8);
+  const int nk = (int)((g.K + BK - 1) / BK);
+  const SplitPlan plan = plan_split(tiles, nk, BM, BN, ws ? ws_bytes : 0);
+  const bool split = plan.tail > 0;
+  g.whole_tiles = split ? plan.whole : (int)tiles;
+  g.split = split ? plan.split : 1;
+  g.part_slabs = split ? plan.part_slabs : nk;
+  g.partial = (float *)ws;
+  g.per_xcd = (g.whole_tiles + 7) / 8;
+  const unsigned grid = (unsigned)(g.per_xcd * 8 + (split ? plan.tail * plan.split : 0));
   constexpr int stages = 2 * (BM + BN) * BK * 2, image = (BM / WGM) * BN * 4;
   constexpr int smem = stages > image ? stages : image;
   static bool attr_set = false;
@@ -352,50 +432,64 @@ int launch_k(const GemmArgs &in, hipStream_t st) {
       return MTNLG_HIP_ERROR;
     attr_set = true;
   }
-  gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL>
-      <<<dim3((unsigned)(g.per_xcd * 8)), 64 * WGM * WGN, smem, st>>>(g);
-  return check_launch();
+  gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL><<<dim3(grid), 64 * WGM * WGN, smem, st>>>(g);
+  MTNLG_TRY(check_launch());
+  if (split) {
+    splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
+    MTNLG_TRY(check_launch());
+  }
+  return MTNLG_OK;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AT, bool BT>
-int launch(const GemmArgs &g, hipStream_t st) {
-  return g.K % BK ? launch_k<BM, BN, WGM, WGN, AT, BT, true>(g, st)
-                  : launch_k<BM, BN, WGM, WGN, AT, BT, false>(g, st);
+int launch(const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
+  return g.K % BK ? launch_k<BM, BN, WGM, WGN, AT, BT, true>(g, ws, ws_bytes, st)
+                  : launch_k<BM, BN, WGM, WGN, AT, BT, false>(g, ws, ws_bytes, st);
 }
 
 // Tile shapes on offer: {BM, BN, waves_m, waves_n}
 enum TileConfig { T256x256_2x2 = 0, T128x128_2x2, T256x256_2x4, T256x128_2x2, T128x256_2x2, TILE_CONFIGS };
 
 template <bool AT, bool BT>
-int launch_config(int cfg, const GemmArgs &g, hipStream_t st) {
+int launch_config(int cfg, const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
   switch (cfg) {
-    case T256x256_2x2: return launch<256, 256, 2, 2, AT, BT>(g, st);
-    case T128x128_2x2: return launch<128, 128, 2, 2, AT, BT>(g, st);
-    case T256x256_2x4: return launch<256, 256, 2, 4, AT, BT>(g, st);
-    case T256x128_2x2: return launch<256, 128, 2, 2, AT, BT>(g, st);
-    case T128x256_2x2: return launch<128, 256, 2, 2, AT, BT>(g, st);
+    case T256x256_2x2: return launch<256, 256, 2, 2, AT, BT>(g, ws, ws_bytes, st);
+    case T128x128_2x2: return launch<128, 128, 2, 2, AT, BT>(g, ws, ws_bytes, st);
+    case T256x256_2x4: return launch<256, 256, 2, 4, AT, BT>(g, ws, ws_bytes, st);
+    case T256x128_2x2: return launch<256, 128, 2, 2, AT, BT>(g, ws, ws_bytes, st);
+    case T128x256_2x2: return launch<128, 256, 2, 2, AT, BT>(g, ws, ws_bytes, st);
     default: return MTNLG_INVALID_ARG;
   }
 }
 
 template <bool AT, bool BT>
-int pick_tile(const GemmArgs &g, hipStream_t st) {
+int pick_tile(const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
   // MTNLG_GEMM_TILE=<0..4> forces one tile shape (tuning aid).
   static const int forced = [] {
     const char *e = getenv("MTNLG_GEMM_TILE");
     return e ? atoi(e) : -1;
   }();
-  if (forced >= 0 && forced < TILE_CONFIGS) return launch_config<AT, BT>(forced, g, st);
-  // 256x256 tiles on 8 waves measure fastest per tile; problems too small to give
-  // most of the 256 CUs one such tile take 128x128 tiles (two workgroups per CU).
+  if (forced >= 0 && forced < TILE_CONFIGS) return launch_config<AT, BT>(forced, g, ws, ws_bytes, st);
+  // 256x256 tiles on 8 waves measure fastest per tile.  A last round that would leave
+  // most CUs idle is split along K instead (needs workspace); without workspace, problems
+  // too small to give most CUs one big tile take 128x128 tiles (two workgroups per CU).
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  return launch_config<AT, BT>(tiles256 < 160 ? T128x128_2x2 : T256x256_2x4, g, st);
+  const int nk = (int)((g.K + BK - 1) / BK);
+  const SplitPlan plan = plan_split(tiles256, nk, 256, 256, ws ? ws_bytes : 0);
+  if (plan.tail == 0 && tiles256 < 160) return launch_config<AT, BT>(T128x128_2x2, g, ws, ws_bytes, st);
+  return launch_config<AT, BT>(T256x256_2x4, g, ws, ws_bytes, st);
 }
 
 }  // namespace
 
+size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+  return plan_split(tiles256, (int)((K + BK - 1) / BK), 256, 256, 0).workspace;
+}
+
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
-                   const void *bias, void *aux, uint32_t epi, hipStream_t stream) {
+                   const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes, hipStream_t stream) {
   if (K % 8 || N % 8) return MTNLG_UNSUPPORTED_SHAPE;
   const bool at = layout == MTNLG_GEMM_TN, bt = layout != MTNLG_GEMM_NT;
   if ((at && (M % 8 || M < 8)) || (bt && (N % 8 || N < 8))) return MTNLG_UNSUPPORTED_SHAPE;
@@ -407,10 +501,11 @@ int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, c
   g.C = C; g.ldc = N;
   g.ea = EpiArgs{bias, aux, epi};
   g.tiles_m = g.tiles_n = g.per_xcd = 0;
+  g.whole_tiles = 0; g.split = 1; g.part_slabs = 0; g.partial = nullptr;
   LaunchScope scope(MTNLG_K_GEMM_NT + layout, stream);
-  if (!at && !bt) return pick_tile<false, false>(g, stream);
-  if (!at && bt) return pick_tile<false, true>(g, stream);
-  return pick_tile<true, true>(g, stream);
+  if (!at && !bt) return pick_tile<false, false>(g, ws, ws_bytes, stream);
+  if (!at && bt) return pick_tile<false, true>(g, ws, ws_bytes, stream);
+  return pick_tile<true, true>(g, ws, ws_bytes, stream);
 }
 
 }  // namespace mtnlg

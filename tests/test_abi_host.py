@@ -83,9 +83,9 @@ def test_null_pointers_and_small_workspace_are_reported_before_any_gpu_work():
     assert L.mtnlg_layer_bwd(ctypes.byref(d), ctypes.byref(tbl), one, one, one, one, ctypes.byref(tbl), one, 1 << 40, nohook, None, None) == -1
     assert L.mtnlg_stage_step(ctypes.byref(d), 0, ctypes.byref(tbl), one, one, two, two, ctypes.byref(tbl), one, 1 << 40, one, 1 << 40, nohook, None, None) == -1
     assert L.mtnlg_stage_step(ctypes.byref(d), 1, ctypes.byref(tbl), one, one, two, two, ctypes.byref(tbl), one, 8, one, 1 << 40, nohook, None, None) == -4
-    assert L.mtnlg_gemm(1, 0, 8, 8, 8, None, one, one, None, None, 0, None) == -2
-    assert L.mtnlg_gemm(1, 5, 8, 8, 8, one, one, one, None, None, 0, None) == -1
-    assert L.mtnlg_gemm(1, 0, 8, 8, 8, one, one, one, None, None, B.EPI_BIAS, None) == -2
+    assert L.mtnlg_gemm(1, 0, 8, 8, 8, None, one, one, None, None, 0, None, 0, None) == -2
+    assert L.mtnlg_gemm(1, 5, 8, 8, 8, one, one, one, None, None, 0, None, 0, None) == -1
+    assert L.mtnlg_gemm(1, 0, 8, 8, 8, one, one, one, None, None, B.EPI_BIAS, None, 0, None) == -2
     assert L.mtnlg_layernorm_fwd(1, 4, 12, one, None, None, one, one, 1e-5, None, one, one, one, None) == -3
     assert L.mtnlg_attention_fwd(1, 1, 8, 1, 8, 0.0, one, one, one, None) == -1
     assert L.mtnlg_colsum(1, 4, 12, one, one, 0, 0, one, None) == -3

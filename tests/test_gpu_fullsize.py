@@ -61,7 +61,9 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
     aux = torch.randn((Mm, N), generator=g, device="cuda").bfloat16() if epi & (B.EPI_RESIDUAL | B.EPI_GELU) else None
     C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
     res = aux.clone() if epi & B.EPI_RESIDUAL else None
-    M.mtnlg_gemm(layout, A, Bm, C, bias=bias, aux=aux, epilogue=epi)
+    need = M.mtnlg_gemm_workspace(B.BF16, layout, Mm, N, K)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+    M.mtnlg_gemm(layout, A, Bm, C, bias=bias, aux=aux, epilogue=epi, workspace=ws)
     rows = sorted({r for r in (0, 1, 127, 128, 255, 256, Mm // 2 + 3, Mm - 129, Mm - 1)})
     cols = sorted({c for c in (0, 7, 255, 256, N // 2 + 5, N - 257, N - 1)})
     An, Bn = to_np(A), to_np(Bm)
