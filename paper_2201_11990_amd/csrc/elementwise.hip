@@ -7,35 +7,40 @@
 
 namespace mtnlg {
 
-// Sum over the 256 threads of a workgroup; result valid in every thread.
-__device__ __forceinline__ float block_sum_256(float v, float *lds4) {
+// Sum over the NTHR threads of a workgroup; result valid in every thread.
+template <int NTHR>
+__device__ __forceinline__ float block_sum(float v, float *lds) {
+  constexpr int NW = NTHR / 64;
   v = wave_sum(v);
-  __syncthreads();  // protects lds4 against a previous use
-  if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+  __syncthreads();  // protects lds against a previous use
+  if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
   __syncthreads();
-  return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+  float s = 0.0f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) s += lds[w];
+  return s;
 }
 
 // ---------------------------------------------------------------- LayerNorm fwd
-// One workgroup per token row; the row lives in registers (NV groups of 8 per
-// thread).  v = x (+ partial + bias); optional xsum = v; out = LN(v).
-template <typename E, int NV>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(int64_t h, const E *__restrict__ x,
-                                                     const E *__restrict__ partial,
-                                                     const E *__restrict__ bias,
-                                                     const E *__restrict__ gamma,
-                                                     const E *__restrict__ beta, float eps,
-                                                     E *__restrict__ xsum, E *__restrict__ out,
-                                                     float *__restrict__ mean,
-                                                     float *__restrict__ rstd) {
-  __shared__ float red[4];
+// One workgroup of NTHR threads per token row; the row lives in registers (NV groups
+// of 8 per thread).  v = x (+ partial + bias); optional xsum = v; out = LN(v).
+template <typename E, int NTHR, int NV>
+__global__ __launch_bounds__(NTHR) void ln_fwd_kernel(int64_t h, const E *__restrict__ x,
+                                                      const E *__restrict__ partial,
+                                                      const E *__restrict__ bias,
+                                                      const E *__restrict__ gamma,
+                                                      const E *__restrict__ beta, float eps,
+                                                      E *__restrict__ xsum, E *__restrict__ out,
+                                                      float *__restrict__ mean,
+                                                      float *__restrict__ rstd) {
+  __shared__ float red[NTHR / 64];
   const int64_t row = blockIdx.x;
   const int nvec = (int)(h / 8);
   float v[NV][8];
   float s = 0.0f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int j = threadIdx.x + i * 256;
+    int j = threadIdx.x + i * NTHR;
     if (j < nvec) {
       load8(x + row * h + (int64_t)j * 8, v[i]);
       if (partial) {
@@ -62,17 +67,17 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int64_t h, const E *__restr
       for (int e = 0; e < 8; ++e) v[i][e] = 0.0f;
     }
   }
-  const float mu = block_sum_256(s, red) / (float)h;
+  const float mu = block_sum<NTHR>(s, red) / (float)h;
   float q = 0.0f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int j = threadIdx.x + i * 256;
+    int j = threadIdx.x + i * NTHR;
     if (j < nvec) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mu) * (v[i][e] - mu);
     }
   }
-  const float var = block_sum_256(q, red) / (float)h;
+  const float var = block_sum<NTHR>(q, red) / (float)h;
   const float rs = rsqrtf(var + eps);
   if (threadIdx.x == 0) {
     mean[row] = mu;
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int64_t h, const E *__restr
   }
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int j = threadIdx.x + i * 256;
+    int j = threadIdx.x + i * NTHR;
     if (j < nvec) {
       float g[8], b[8], o[8];
       load8(gamma + (int64_t)j * 8, g);
@@ -96,67 +101,110 @@ template <typename E>
 static int ln_fwd_launch(int64_t T, int64_t h, const void *x, const void *partial, const void *bias,
                          const void *gamma, const void *beta, float eps, void *xsum, void *out,
                          float *mean, float *rstd, hipStream_t st) {
-  const int nv = (int)((h / 8 + 255) / 256);
-#define LNF(NV)                                                                                   \
-  ln_fwd_kernel<E, NV><<<dim3((unsigned)T), 256, 0, st>>>(                                        \
+  const int nvec = (int)(h / 8);
+#define LNF(NTHR, NV)                                                                             \
+  ln_fwd_kernel<E, NTHR, NV><<<dim3((unsigned)T), NTHR, 0, st>>>(                                 \
       h, (const E *)x, (const E *)partial, (const E *)bias, (const E *)gamma, (const E *)beta, eps, \
       (E *)xsum, (E *)out, mean, rstd)
   LaunchScope scope(MTNLG_K_LN_FWD, st);
-  if (nv <= 1) LNF(1);
-  else if (nv <= 2) LNF(2);
-  else if (nv <= 4) LNF(4);
-  else if (nv <= 8) LNF(8);
-  else if (nv <= 16) LNF(16);
+  if (nvec <= 256) LNF(256, 1);
+  else if (nvec <= 512) LNF(256, 2);
+  else if (nvec <= 1024) LNF(256, 4);
+  else if (nvec <= 2048) LNF(1024, 2);
+  else if (nvec <= 3072) LNF(1024, 3);
+  else if (nvec <= 4096) LNF(1024, 4);
   else return MTNLG_UNSUPPORTED_SHAPE;
 #undef LNF
   return check_launch();
 }
 
 // ---------------------------------------------------------------- LayerNorm bwd
-// Row part: dx = dres + rs * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dout * gamma.
-template <typename E, int NV>
-__global__ __launch_bounds__(256) void ln_bwd_row_kernel(int64_t h, const E *__restrict__ x,
-                                                         const E *__restrict__ gamma,
-                                                         const float *__restrict__ mean,
-                                                         const float *__restrict__ rstd,
-                                                         const E *__restrict__ dout,
-                                                         const E *__restrict__ dres,
-                                                         E *__restrict__ dx) {
-  __shared__ float red[4];
-  const int64_t row = blockIdx.x;
+// One 1024-thread workgroup walks `rows_per` consecutive token rows; a thread owns the
+// same NV groups of 8 columns in every row, so the column sums
+//   dgamma = sum_t dout*xhat,  dbeta = sum_t dout,  (CS) colsum = sum_t dx
+// build up in its registers while the rows stream through once from HBM:
+//   pass 1 over the row: xhat, dxh = dout*gamma -> row sums m1 = mean(dxh), m2 = mean(dxh*xhat)
+//   pass 2 (row re-read, L2-resident): dx = dres + rs * (dxh - m1 - xhat*m2)
+// Workgroup b leaves its column sums in ws[o][b][h]; a second kernel adds them in a
+// fixed order.
+constexpr int LNB_THREADS = 1024, LNB_MAX_WGS = 256;
+
+template <typename E, int NV, bool CS>
+__global__ __launch_bounds__(LNB_THREADS) void ln_bwd_fused_kernel(
+    int64_t T, int64_t h, int rows_per, const E *__restrict__ x, const E *__restrict__ gamma,
+    const float *__restrict__ mean, const float *__restrict__ rstd, const E *__restrict__ dout,
+    const E *__restrict__ dres, E *__restrict__ dx, float *__restrict__ ws) {
+  __shared__ float red[2][LNB_THREADS / 64];
   const int nvec = (int)(h / 8);
-  const float mu = mean[row], rs = rstd[row];
-  float xh[NV][8], dh[NV][8];
-  float s1 = 0.0f, s2 = 0.0f;
+  const int64_t row0 = (int64_t)blockIdx.x * rows_per;
+  const int64_t row1 = row0 + rows_per < T ? row0 + rows_per : T;
+  float dg[NV][8] = {}, db[NV][8] = {}, cs[CS ? NV : 1][8] = {};
+  for (int64_t row = row0; row < row1; ++row) {
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    int j = threadIdx.x + i * 256;
-    if (j < nvec) {
-      float g[8];
-      load8(x + row * h + (int64_t)j * 8, xh[i]);
-      load8(dout + row * h + (int64_t)j * 8, dh[i]);
-      load8(gamma + (int64_t)j * 8, g);
+    for (int i = 0; i < NV; ++i) {
+      const int j = threadIdx.x + i * LNB_THREADS;
+      if (j < nvec) {
+        float xv[8], dv[8], g[8];
+        load8(x + row * h + (int64_t)j * 8, xv);
+        load8(dout + row * h + (int64_t)j * 8, dv);
+        load8(gamma + (int64_t)j * 8, g);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        xh[i][e] = (xh[i][e] - mu) * rs;
-        dh[i][e] *= g[e];
-        s1 += dh[i][e];
-        s2 += dh[i][e] * xh[i][e];
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (xv[e] - mu) * rs, dh = dv[e] * g[e];
+          s1 += dh;
+          s2 += dh * xh;
+          dg[i][e] += dv[e] * xh;
+          db[i][e] += dv[e];
+        }
+      }
+    }
+    // both row sums through one pair of barriers
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+      red[0][threadIdx.x >> 6] = s1;
+      red[1][threadIdx.x >> 6] = s2;
+    }
+    __syncthreads();
+    float m1 = 0.0f, m2 = 0.0f;
+#pragma unroll
+    for (int w = 0; w < LNB_THREADS / 64; ++w) {
+      m1 += red[0][w];
+      m2 += red[1][w];
+    }
+    m1 /= (float)h;
+    m2 /= (float)h;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int j = threadIdx.x + i * LNB_THREADS;
+      if (j < nvec) {
+        float xv[8], dv[8], g[8], o[8];
+        load8(x + row * h + (int64_t)j * 8, xv);
+        load8(dout + row * h + (int64_t)j * 8, dv);
+        load8(gamma + (int64_t)j * 8, g);
+        if (dres) load8(dres + row * h + (int64_t)j * 8, o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (xv[e] - mu) * rs, dh = dv[e] * g[e];
+          o[e] = (dres ? o[e] : 0.0f) + rs * (dh - m1 - xh * m2);
+          if constexpr (CS) cs[i][e] += to_f32(from_f32<E>(o[e]));  // the stored value
+        }
+        store8(dx + row * h + (int64_t)j * 8, o);
       }
     }
   }
-  const float m1 = block_sum_256(s1, red) / (float)h;
-  const float m2 = block_sum_256(s2, red) / (float)h;
+  const int64_t stride = (int64_t)gridDim.x * h;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    int j = threadIdx.x + i * 256;
+    const int j = threadIdx.x + i * LNB_THREADS;
     if (j < nvec) {
-      float o[8], r[8];
-      if (dres) load8(dres + row * h + (int64_t)j * 8, r);
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        o[e] = (dres ? r[e] : 0.0f) + rs * (dh[i][e] - m1 - xh[i][e] * m2);
-      store8(dx + row * h + (int64_t)j * 8, o);
+      float *o = ws + (int64_t)blockIdx.x * h + (int64_t)j * 8;
+      store8(o, dg[i]);
+      store8(o + stride, db[i]);
+      if constexpr (CS) store8(o + 2 * stride, cs[i]);
     }
   }
 }
@@ -222,16 +270,36 @@ __global__ __launch_bounds__(256) void colreduce_stage1(int64_t T, int64_t C,
   }
 }
 
-// Stage 2: out[c] (+)= sum_r ws[o][r][c]
+// Stage 2: out_o[c] (+)= sum_r ws[o][r][c] for up to three outputs o = blockIdx.y.
+// A workgroup owns 64 columns; wave w adds rows w, w+4, ... in order, the four wave
+// sums are then added in order: a fixed summation tree, independent of scheduling.
+struct Stage2Outs {
+  void *out[3];
+};
 template <typename O>
-__global__ void colreduce_stage2(int64_t C, int nrb, const float *__restrict__ ws, O *out,
-                                 int accumulate) {
-  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
-  float s = 0.0f;
-  for (int r = 0; r < nrb; ++r) s += ws[(int64_t)r * C + c];
-  if (accumulate) s += to_f32(out[c]);
-  out[c] = from_f32<O>(s);
+__global__ __launch_bounds__(256) void colreduce_stage2(int64_t C, int nrb, const float *__restrict__ ws,
+                                                        Stage2Outs outs, int accumulate) {
+  __shared__ float part[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  const float *src = ws + (int64_t)blockIdx.y * nrb * C;
+  float s0 = 0.0f, s1 = 0.0f;
+  if (c < C) {
+    int r = wave;
+    for (; r + 4 < nrb; r += 8) {
+      s0 += src[(int64_t)r * C + c];
+      s1 += src[(int64_t)(r + 4) * C + c];
+    }
+    if (r < nrb) s0 += src[(int64_t)r * C + c];
+  }
+  part[wave][lane] = s0 + s1;
+  __syncthreads();
+  if (wave == 0 && c < C) {
+    float s = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+    O *out = static_cast<O *>(outs.out[blockIdx.y]);
+    if (accumulate) s += to_f32(out[c]);
+    out[c] = from_f32<O>(s);
+  }
 }
 
 static int colreduce_rowblocks(int64_t T) {
@@ -241,49 +309,50 @@ static int colreduce_rowblocks(int64_t T) {
   return (int)rb;
 }
 
+// ws holds nout consecutive [nrb][C] partial blocks; outs their destinations.
 template <typename E>
-static void stage2_launch(int64_t C, int nrb, const float *ws, void *out, int out_f32, int accumulate,
-                          hipStream_t st) {
-  dim3 grid((unsigned)((C + 255) / 256));
+static void stage2_launch(int64_t C, int nrb, const float *ws, int nout, void *o0, void *o1, void *o2,
+                          int out_f32, int accumulate, hipStream_t st) {
+  dim3 grid((unsigned)((C + 63) / 64), (unsigned)nout);
+  Stage2Outs outs{{o0, o1, o2}};
   if (out_f32)
-    colreduce_stage2<float><<<grid, 256, 0, st>>>(C, nrb, ws, (float *)out, accumulate);
+    colreduce_stage2<float><<<grid, 256, 0, st>>>(C, nrb, ws, outs, accumulate);
   else
-    colreduce_stage2<E><<<grid, 256, 0, st>>>(C, nrb, ws, (E *)out, accumulate);
+    colreduce_stage2<E><<<grid, 256, 0, st>>>(C, nrb, ws, outs, accumulate);
 }
+
+static int ln_bwd_workgroups(int64_t T) { return (int)(T < LNB_MAX_WGS ? T : LNB_MAX_WGS); }
 
 template <typename E>
 static int ln_bwd_launch(int64_t T, int64_t h, const void *x, const void *gamma, const float *mean,
                          const float *rstd, const void *dout, const void *dres, void *dx,
                          void *dgamma, void *dbeta, void *colsum_dx, int grad_f32, int accumulate,
                          void *workspace, hipStream_t st) {
-  const int nv = (int)((h / 8 + 255) / 256);
-#define LNB(NV)                                                                          \
-  ln_bwd_row_kernel<E, NV><<<dim3((unsigned)T), 256, 0, st>>>(                           \
-      h, (const E *)x, (const E *)gamma, mean, rstd, (const E *)dout, (const E *)dres, (E *)dx)
-  {
-    LaunchScope scope(MTNLG_K_LN_BWD, st);
-    if (nv <= 1) LNB(1);
-    else if (nv <= 2) LNB(2);
-    else if (nv <= 4) LNB(4);
-    else if (nv <= 8) LNB(8);
-    else if (nv <= 16) LNB(16);
+  const int nvec = (int)(h / 8);
+  const int rows_per = (int)((T + LNB_MAX_WGS - 1) / LNB_MAX_WGS);
+  const int nwg = (int)((T + rows_per - 1) / rows_per);  // <= ln_bwd_workgroups(T)
+  float *ws = (float *)workspace;
+#define LNB(NV, CS)                                                                                  \
+  ln_bwd_fused_kernel<E, NV, CS><<<dim3((unsigned)nwg), LNB_THREADS, 0, st>>>(                       \
+      T, h, rows_per, (const E *)x, (const E *)gamma, mean, rstd, (const E *)dout, (const E *)dres, \
+      (E *)dx, ws)
+  LaunchScope scope(MTNLG_K_LN_BWD, st);
+  if (colsum_dx) {
+    if (nvec <= 1024) LNB(1, true);
+    else if (nvec <= 2048) LNB(2, true);
+    else if (nvec <= 3072) LNB(3, true);
+    else if (nvec <= 4096) LNB(4, true);
     else return MTNLG_UNSUPPORTED_SHAPE;
-    MTNLG_TRY(check_launch());
+  } else {
+    if (nvec <= 1024) LNB(1, false);
+    else if (nvec <= 2048) LNB(2, false);
+    else if (nvec <= 3072) LNB(3, false);
+    else if (nvec <= 4096) LNB(4, false);
+    else return MTNLG_UNSUPPORTED_SHAPE;
   }
 #undef LNB
-  const int nrb = colreduce_rowblocks(T);
-  float *ws = (float *)workspace;
-  dim3 grid((unsigned)((h + CR_COLS - 1) / CR_COLS), (unsigned)nrb);
-  {
-    LaunchScope scope(MTNLG_K_LN_BWD, st);
-    colreduce_stage1<E, 1><<<grid, 256, 0, st>>>(T, h, (const E *)dout, (const E *)x, mean, rstd,
-                                                 colsum_dx ? (const E *)dx : nullptr, ws);
-    MTNLG_TRY(check_launch());
-  }
-  LaunchScope scope(MTNLG_K_LN_BWD, st);
-  stage2_launch<E>(h, nrb, ws, dgamma, grad_f32, accumulate, st);
-  stage2_launch<E>(h, nrb, ws + (int64_t)nrb * h, dbeta, grad_f32, accumulate, st);
-  if (colsum_dx) stage2_launch<E>(h, nrb, ws + 2 * (int64_t)nrb * h, colsum_dx, grad_f32, accumulate, st);
+  MTNLG_TRY(check_launch());
+  stage2_launch<E>(h, nwg, ws, colsum_dx ? 3 : 2, dgamma, dbeta, colsum_dx, grad_f32, accumulate, st);
   return check_launch();
 }
 
@@ -296,7 +365,7 @@ static int colsum_launch(int64_t T, int64_t C, const void *in, void *out, int ou
   colreduce_stage1<E, 0><<<grid, 256, 0, st>>>(T, C, (const E *)in, nullptr, nullptr, nullptr, nullptr,
                                                (float *)workspace);
   MTNLG_TRY(check_launch());
-  stage2_launch<E>(C, nrb, (const float *)workspace, out, out_f32, accumulate, st);
+  stage2_launch<E>(C, nrb, (const float *)workspace, 1, out, nullptr, nullptr, out_f32, accumulate, st);
   return check_launch();
 }
 
@@ -377,7 +446,7 @@ int mtnlg_layernorm_fwd(int dtype, int64_t T, int64_t h, const void *x, const vo
 
 size_t mtnlg_layernorm_bwd_workspace(int64_t T, int64_t h) {
   if (T <= 0 || h <= 0) return 0;
-  return (size_t)3 * colreduce_rowblocks(T) * (size_t)h * sizeof(float);
+  return (size_t)3 * ln_bwd_workgroups(T) * (size_t)h * sizeof(float);
 }
 
 int mtnlg_layernorm_bwd(int dtype, int64_t T, int64_t h, const void *x, const void *gamma,
