@@ -110,6 +110,9 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int t) {
 // row index inside a 32x32 block of accumulator register e for lane group g
 __device__ __forceinline__ int acc_row(int e, int g) { return 8 * (e >> 2) + 4 * g + (e & 3); }
 
+// 2^x on the transcendental unit (v_exp_f32): no denormal fix-up, 2^-inf = 0.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
 // ------------------------------------------------------------------ forward
@@ -167,36 +170,42 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk)
           sacc[blk] = MFMA(frag_nat<D>(Kt, blk * 32 + (lane & 31), 2 * kk + g), qf[kk], sacc[blk]);
-      const bool diag = kv0 + 63 > qw;  // wave-uniform: masking needed
+      // m tracks the running maximum of the raw scores; exponents are taken in base 2
+      // with the scale folded in: p = 2^(s*c - m*c).
+      if (kv0 + 63 > qw) {  // wave-uniform: this tile crosses the diagonal for some row
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (kv0 + blk * 32 + acc_row(e, g) > qc) sacc[blk][e] = -INFINITY;
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float v = sacc[blk][e] * c;
-          if (diag && kv0 + blk * 32 + acc_row(e, g) > qc) v = -INFINITY;
-          sacc[blk][e] = v;
-          mx = fmaxf(mx, v);
-        }
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[blk][e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m, mx);  // finite from the first tile on (key 0 is never masked)
-      const float alpha = exp2f(m - m_new);
+      const float mc = m_new * c;
       float rs = 0.0f;
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          float p = exp2f(sacc[blk][e] - m_new);
+          const float p = fast_exp2(fmaf(sacc[blk][e], c, -mc));
           sacc[blk][e] = p;
           rs += p;
         }
       rs += __shfl_xor(rs, 32, 64);
+      const float alpha = fast_exp2((m - m_new) * c);
       l = l * alpha + rs;
+      if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {  // some row's maximum moved: rescale O
+#pragma unroll
+        for (int db = 0; db < DBK; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+      }
       m = m_new;
-#pragma unroll
-      for (int db = 0; db < DBK; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
         for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[db][4 * e4 + i] * inv);
         *reinterpret_cast<bf16x4 *>(out + db * 32 + 8 * e4 + 4 * g) = o;
       }
-    if (g == 0) lse[((int64_t)bi * n + j) * s + q] = (m + log2f(l)) * kLn2;
+    if (g == 0) lse[((int64_t)bi * n + j) * s + q] = (m * c + log2f(l)) * kLn2;
   }
 }
 
@@ -302,14 +311,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
           pacc[blk] = MFMA(frag_nat<D>(Vn, blk * 32 + (lane & 31), 2 * kk + g), dof[kk], pacc[blk]);
         }
       // dS^T = P^T o (dP^T - D)
+      if (kv0 + 63 > qw) {  // wave-uniform: diagonal (or past-the-end keys) in this tile
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+        for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int kv = kv0 + blk * 32 + acc_row(e, g);
-          float p = kv > qc ? 0.0f : exp2f(sacc[blk][e] * c - lse2);
-          sacc[blk][e] = p * (pacc[blk][e] - dsum);
-        }
+          for (int e = 0; e < 16; ++e) {
+            const int kv = kv0 + blk * 32 + acc_row(e, g);
+            const float p = kv > qc ? 0.0f : fast_exp2(fmaf(sacc[blk][e], c, -lse2));
+            sacc[blk][e] = p * (pacc[blk][e] - dsum);
+          }
+      } else {
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            sacc[blk][e] = fast_exp2(fmaf(sacc[blk][e], c, -lse2)) * (pacc[blk][e] - dsum);
+      }
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
@@ -405,16 +422,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
           pacc[qb2] = MFMA(frag_nat<D>(On, qb2 * 32 + (lane & 31), 2 * kk + g), vf[kk], pacc[qb2]);
         }
       // element (register e, lane) is query q0 + 32*qb2 + acc_row(e,g), key = this lane's key
+      if (q0 < kw + 32 || q0 + 63 >= s) {  // wave-uniform: diagonal or past-the-end queries
 #pragma unroll
-      for (int qb2 = 0; qb2 < 2; ++qb2)
+        for (int qb2 = 0; qb2 < 2; ++qb2)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int ql = qb2 * 32 + acc_row(e, g);
-          const int qq = q0 + ql;
-          float p = (qq < key || qq >= s) ? 0.0f : exp2f(sacc[qb2][e] * c - stat[ql]);
-          sacc[qb2][e] = p;
-          pacc[qb2][e] = p * (pacc[qb2][e] - stat[64 + ql]);
-        }
+          for (int e = 0; e < 16; ++e) {
+            const int ql = qb2 * 32 + acc_row(e, g);
+            const int qq = q0 + ql;
+            const float p = (qq < key || qq >= s) ? 0.0f : fast_exp2(fmaf(sacc[qb2][e], c, -stat[ql]));
+            sacc[qb2][e] = p;
+            pacc[qb2][e] = p * (pacc[qb2][e] - stat[64 + ql]);
+          }
+      } else {
+#pragma unroll
+        for (int qb2 = 0; qb2 < 2; ++qb2)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int ql = qb2 * 32 + acc_row(e, g);
+            const float p = fast_exp2(fmaf(sacc[qb2][e], c, -stat[ql]));
+            sacc[qb2][e] = p;
+            pacc[qb2][e] = p * (pacc[qb2][e] - stat[64 + ql]);
+          }
+      }
 #pragma unroll
       for (int qb2 = 0; qb2 < 2; ++qb2)
 #pragma unroll
