@@ -58,8 +58,10 @@ template <int ROWS, int NTHR>
 struct LoadK {
   static constexpr int N = ROWS * 8 / NTHR;
   i32x4 r[N];
+  static constexpr int LDS_WRITES = N;
   template <bool KTAIL>
-  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K) {
+  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K,
+                                        char *) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       int q = threadIdx.x + NTHR * i;
@@ -85,6 +87,33 @@ struct LoadK {
   }
 };
 
+// K-contiguous source, straight into LDS (global_load_lds_dwordx4): a wave instruction
+// fills 1 KB = 8 tile rows; lane l supplies the address of the chunk that belongs at
+// LDS slot l of that KB under the tile's swizzle.  No registers, no LDS write
+// instructions; completion is tracked by vmcnt.  K % 64 == 0 only.
+template <int ROWS, int NTHR>
+struct LoadKDirect {
+  static constexpr int NI = ROWS / 8 / (NTHR / 64);  // instructions per wave
+  static constexpr int LDS_WRITES = 0;
+  template <bool KTAIL>
+  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t,
+                                        char *lds) {
+    static_assert(!KTAIL, "direct-to-LDS loads cannot zero-fill a K tail");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave * NI + i;
+      const int row = 8 * q + (lane >> 3);
+      const int c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
+      const int64_t rr = row < rows_valid ? row : rows_valid - 1;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)(base + rr * ld + k0 + c * 8),
+          (__attribute__((address_space(3))) void *)(lds + q * 1024), 16, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void stash(char *) const {}
+};
+
 // Row-contiguous source ([k][row] in memory): each thread owns KB k-rows x 8 rows.
 // A wave covers 8 row-blocks x 8 k-blocks, which spreads its transposed LDS writes
 // evenly over the banks.
@@ -101,8 +130,10 @@ struct LoadT {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     return (wave / RBH) * 8 + (lane >> 3);
   }
+  static constexpr int LDS_WRITES = 8;
   template <bool KTAIL>
-  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K) {
+  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int64_t rows_valid, int64_t k0, int64_t K,
+                                        char *) {
     const int rb = row_block(), kb = k_block();
     int64_t row = rb * 8;
     if (row + 8 > rows_valid) row = rows_valid - 8;  // rows_valid >= 8 and a multiple of 8
@@ -144,12 +175,14 @@ __device__ __forceinline__ void sched_pairs() {
   }
 }
 
-template <int ROWS, int NTHR, bool T>
+template <int ROWS, int NTHR, bool T, bool DIRECT>
 struct Loader;
 template <int ROWS, int NTHR>
-struct Loader<ROWS, NTHR, false> : LoadK<ROWS, NTHR> {};
+struct Loader<ROWS, NTHR, false, false> : LoadK<ROWS, NTHR> {};
 template <int ROWS, int NTHR>
-struct Loader<ROWS, NTHR, true> : LoadT<ROWS, NTHR> {};
+struct Loader<ROWS, NTHR, false, true> : LoadKDirect<ROWS, NTHR> {};
+template <int ROWS, int NTHR, bool D>
+struct Loader<ROWS, NTHR, true, D> : LoadT<ROWS, NTHR> {};
 
 // Bias / GeLU / residual / accumulate / store for 8 consecutive outputs of row m at column n.
 __device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t n, float (&v)[8]) {
@@ -237,8 +270,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   const bf16 *Bbase = BT ? g.B + n0 : g.B + n0 * g.ldb;
   const int64_t a_rows = g.M - m0, b_rows = g.N - n0;
 
-  Loader<BM, NTHR, AT> la;
-  Loader<BN, NTHR, BT> lb;
+  // K-contiguous operands go straight to LDS when K has no tail
+  constexpr bool DIRECT_A = !AT && !KTAIL, DIRECT_B = !BT && !KTAIL;
+  Loader<BM, NTHR, AT, DIRECT_A> la;
+  Loader<BN, NTHR, BT, DIRECT_B> lb;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -265,10 +300,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   };
 
   const int nk = slab1 - slab0;
-  la.template fetch<KTAIL>(Abase, g.lda, a_rows, (int64_t)slab0 * BK, g.K);
-  lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, (int64_t)slab0 * BK, g.K);
+  la.template fetch<KTAIL>(Abase, g.lda, a_rows, (int64_t)slab0 * BK, g.K, smem);
+  lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, (int64_t)slab0 * BK, g.K, smem + A_BYTES);
   la.stash(smem);
   lb.stash(smem + A_BYTES);
+  if constexpr (DIRECT_A || DIRECT_B) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct loads landed
   __syncthreads();
   read_frags(smem, 0, af[0], bfr[0]);
 
@@ -280,7 +316,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   //              slab are issued under the second half of the MFMAs.
   // The final iteration reloads the last slab instead of branching; nobody reads it.
   constexpr int NM = TM * TN, NR = TM + TN;
-  constexpr int NW = (AT ? 8 : BM * 8 / NTHR) + (BT ? 8 : BN * 8 / NTHR);  // LDS writes per slab
+  constexpr int NW = decltype(la)::LDS_WRITES + decltype(lb)::LDS_WRITES;  // LDS write instructions per slab
   auto mfma_rows = [&](int buf, int i_begin, int i_end) {
 #pragma unroll
     for (int i = i_begin; i < i_end; ++i)
@@ -292,8 +328,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
     const char *cur = smem + (it & 1) * STAGE;
     char *nxt = smem + ((it + 1) & 1) * STAGE;
     const int64_t k_next = (int64_t)(slab0 + (it + 1 < nk ? it + 1 : it)) * BK;
-    la.template fetch<KTAIL>(Abase, g.lda, a_rows, k_next, g.K);
-    lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, k_next, g.K);
+    la.template fetch<KTAIL>(Abase, g.lda, a_rows, k_next, g.K, nxt);
+    lb.template fetch<KTAIL>(Bbase, g.ldb, b_rows, k_next, g.K, nxt + A_BYTES);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < KS - 1; ++kk) {
@@ -310,8 +346,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
     la.stash(nxt);
     lb.stash(nxt + A_BYTES);
     mfma_rows((KS - 1) & 1, 0, TM / 2);
-    sched_pairs<SCHED_MFMA, 1, SCHED_DS_WRITE, NW / (NM / 2), NM / 2>();
+    if constexpr (NW > 0) sched_pairs<SCHED_MFMA, 1, SCHED_DS_WRITE, (NW + NM / 2 - 1) / (NM / 2), NM / 2>();
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DIRECT_A || DIRECT_B) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     read_frags(nxt, 0, af[0], bfr[0]);
