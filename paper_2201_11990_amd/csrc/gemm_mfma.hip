@@ -175,6 +175,25 @@ __device__ __forceinline__ void sched_pairs() {
   }
 }
 
+// Scheduling pipeline of one k-step of the streaming kernel: NM MFMAs, NR LDS fragment reads and NV
+// DMA instructions, spread as evenly as the counts allow (one item after each MFMA).
+template <int NM, int NR, int NV, int M = 0, int R = 0, int V = 0>
+__device__ __forceinline__ void stream_sched() {
+  if constexpr (M < NM) {
+    __builtin_amdgcn_sched_group_barrier(SCHED_MFMA, 1, 0);
+    // after MFMA number M+1: reads so far should be ceil((M+1) NR / NM), loads ceil((M+1) NV / NM) - offset
+    constexpr int r_target = ((M + 1) * NR + NM - 1) / NM;
+    constexpr int v_target = ((2 * M + 1) * NV) / (2 * NM);   // loads trail the reads by half a slot
+    constexpr int dr = r_target - R, dv = v_target - V;
+    if constexpr (dr > 0) __builtin_amdgcn_sched_group_barrier(SCHED_DS_READ, dr, 0);
+    if constexpr (dv > 0) __builtin_amdgcn_sched_group_barrier(0x020, dv, 0);
+    stream_sched<NM, NR, NV, M + 1, R + (dr > 0 ? dr : 0), V + (dv > 0 ? dv : 0)>();
+  } else {
+    if constexpr (R < NR) __builtin_amdgcn_sched_group_barrier(SCHED_DS_READ, NR - R, 0);
+    if constexpr (V < NV) __builtin_amdgcn_sched_group_barrier(0x020, NV - V, 0);
+  }
+}
+
 template <int ROWS, int NTHR, bool T, bool DIRECT>
 struct Loader;
 template <int ROWS, int NTHR>
@@ -396,6 +415,215 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
   }
 }
 
+// =======================================================================================
+// Streaming kernel: 256x256 tile, BK = 64, both operands brought global -> LDS by DMA
+// (buffer_load ... lds), no register staging, no LDS store instructions.
+//   A lives in a ring of two 32 KB stages, B in a ring of three (B is the operand that comes
+//   from HBM for the first time: the weights); the DMA instructions of a slab are spread over
+//   the k-steps (two or four per k-step and wave) so that the texture path never sees a burst.
+//   K-contiguous operand: stage = [256 rows][128 B], 16-byte chunk c of row r at chunk position
+//     c ^ (r & 7) ^ ((r >> 3) & 7); MFMA fragments are 16-byte LDS reads.
+//   Row-contiguous operand ([k][row] in memory): stage = [64 k][512 B] as in memory, 64-byte
+//     granule g of k-row k at granule position g ^ (k & 3); MFMA fragments are two transposing
+//     8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads 4 k-rows x 16 rows and
+//     every lane receives the 4 k values of its own row).
+//   One workgroup barrier per slab, placed before the last k-step (whose fragments are already in
+//   registers) so that the first fragment reads of the next slab hide behind a k-step of MFMAs.
+//   Aligned problems only: M, N multiples of 256, K of 64.
+template <int NWN, bool AT, bool BT>
+__global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int BM = 256, BN = 256, WGM = 2, WGN = NWN, NWAVES = WGM * WGN, NTHR = 64 * NWAVES;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
+  constexpr int STAGE = 256 * BK * 2, A_RING = 2 * STAGE, B_RING = 3 * STAGE;
+  constexpr int NI = 32 / NWAVES;   // DMA instructions per wave per operand and slab
+  const int nk_all = (int)(g.K / BK);
+  int pid, slab0 = 0, slab1 = nk_all, part_id = -1;
+  if ((int)blockIdx.x < 8 * g.per_xcd) {
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    pid = xcd * g.per_xcd + local;
+    if (pid >= g.whole_tiles) return;
+  } else {
+    part_id = blockIdx.x - 8 * g.per_xcd;
+    pid = g.whole_tiles + part_id / g.split;
+    slab0 = (part_id % g.split) * g.part_slabs;
+    slab1 = slab0 + g.part_slabs < nk_all ? slab0 + g.part_slabs : nk_all;
+  }
+  int tm, tn;
+  tile_coords(g, pid, tm, tn);
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const bf16 *Abase = AT ? g.A + m0 : g.A + m0 * g.lda;
+  const bf16 *Bbase = BT ? g.B + n0 : g.B + n0 * g.ldb;
+
+  // DMA addressing.  Wave w issues instructions q = NI w .. NI w + NI - 1 of each operand; instruction
+  // q fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l the 16 bytes at 16 l.
+  uint32_t a_off[NI], b_off[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int q = wave * NI + i;
+    if constexpr (!AT) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
+      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
+      a_off[i] = (uint32_t)(row * g.lda * 2 + c * 16);
+    } else {               // k-rows 2q, 2q+1, lane l: k = 2q + l/32, 16-byte unit l%32
+      const int k = 2 * q + (lane >> 5), u = lane & 31;
+      a_off[i] = (uint32_t)(k * g.lda * 2 + ((((u >> 2) ^ (k & 3)) << 2) | (u & 3)) * 16);
+    }
+    if constexpr (!BT) {
+      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
+      b_off[i] = (uint32_t)(row * g.ldb * 2 + c * 16);
+    } else {
+      const int k = 2 * q + (lane >> 5), u = lane & 31;
+      b_off[i] = (uint32_t)(k * g.ldb * 2 + ((((u >> 2) ^ (k & 3)) << 2) | (u & 3)) * 16);
+    }
+  }
+  auto issue = [&](const bf16 *base, const uint32_t(&off)[NI], char *stage, int i0, int i1) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
+    char *dst = stage + wave * (NI * 1024);
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      if (i >= i0 && i < i1)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16,
+                                                 (int)off[i], 0, 0, 0);
+  };
+  // slab at k0 (elements): where the operand's tile starts
+  auto a_at = [&](int64_t k0) { return AT ? Abase + k0 * g.lda : Abase + k0; };
+  auto b_at = [&](int64_t k0) { return BT ? Bbase + k0 * g.ldb : Bbase + k0; };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // fragment of the 32-row block starting at row r0 for k-step kk
+  auto frag = [&](const char *stage, int r0, int kk, bool transposed) -> bf16x8 {
+    if (!transposed) {
+      const int row = r0 + (lane & 31);
+      return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + swz(row, kk * 2 + (lane >> 5)));
+    } else {
+      // lane = 16 grp + L: as address supplier it covers k-row kbase + L/4, rows nb + 4 (L%4) .. +3
+      const int grp = lane >> 4, L = lane & 15;
+      const int nb = r0 + 16 * (grp & 1) + 4 * (L & 3);
+      const int kbase = 16 * kk + 8 * (grp >> 1) + (L >> 2);
+      i16x4 lo, hi;
+      {
+        const int k = kbase;
+        const char *p = stage + k * 512 + ((((nb >> 5) ^ (k & 3)) << 6) | ((nb & 31) << 1));
+        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
+      }
+      {
+        const int k = kbase + 4;
+        const char *p = stage + k * 512 + ((((nb >> 5) ^ (k & 3)) << 6) | ((nb & 31) << 1));
+        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
+      }
+      i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto read_frags = [&](const char *abuf, const char *bbuf, int kk, bf16x8(&fa)[TM], bf16x8(&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = frag(abuf, wm * WM + i * 32, kk, AT);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = frag(bbuf, wn * WN + j * 32, kk, BT);
+  };
+  auto mfma_rows = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+      }
+  };
+
+  const int nk = slab1 - slab0;
+  auto slab_k = [&](int it) { return (int64_t)(slab0 + (it < nk ? it : nk - 1)) * BK; };
+  char *const aring = smem, *const bring = smem + A_RING;
+  // prologue: A slab 0, B slabs 0 and 1, first half of A slab 1
+  issue(a_at(slab_k(0)), a_off, aring, 0, NI);
+  issue(b_at(slab_k(0)), b_off, bring, 0, NI);
+  issue(b_at(slab_k(1)), b_off, bring + STAGE, 0, NI);
+  issue(a_at(slab_k(1)), a_off, aring + STAGE, 0, NI / 2);
+  if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // A 0, B 0 landed
+  else asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+  read_frags(aring, bring, 0, af[0], bfr[0]);
+
+  int a_cur = 0, b_cur = 0;   // ring offsets of slab `it`
+  for (int it = 0; it < nk; ++it) {
+    const int a_nxt = a_cur ^ STAGE;
+    const int b_nxt = b_cur + STAGE >= B_RING ? b_cur + STAGE - B_RING : b_cur + STAGE;
+    const int b_nn = b_nxt + STAGE >= B_RING ? b_nxt + STAGE - B_RING : b_nxt + STAGE;
+    // k-step 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
+    // k-steps 1, 2: B slab it+2 into the ring stage that held slab it-1
+    // k-step 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      // The two waves of a SIMD take turns on the matrix pipe one k-step at a time: the wave that
+      // is behind (counted from the barrier) has the higher issue priority.
+      if (kk == 0) __builtin_amdgcn_s_setprio(2);
+      else if (kk == 1) __builtin_amdgcn_s_setprio(1);
+      else if (kk == 2) __builtin_amdgcn_s_setprio(0);
+      if (kk == KS - 1) {
+        // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
+        if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        __builtin_amdgcn_s_setprio(3);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(aring + a_nxt, bring + b_nxt, 0, af[0], bfr[0]);
+      } else {
+        read_frags(aring + a_cur, bring + b_cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+      }
+      if (kk == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NI / 2, NI);
+      else if (kk < KS - 1) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (kk - 1) * (NI / 2), kk * (NI / 2));
+      else issue(a_at(slab_k(it + 2)), a_off, aring + a_cur, 0, NI / 2);
+      mfma_rows(kk & 1);
+      stream_sched<TM * TN, (AT ? 2 : 1) * TM + (BT ? 2 : 1) * TN, NI / 2>();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    a_cur = a_nxt;
+    b_cur = b_nxt;
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  __builtin_amdgcn_s_setprio(0);
+
+  float *img = reinterpret_cast<float *>(smem);
+#pragma unroll
+  for (int half = 0; half < WGM; ++half) {
+    if (wm == half) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int row = i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const int col = wn * WN + j * 32 + (lane & 31);
+            img[row * BN + col] = acc[i][j][e];
+          }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < WM * (BN / 8); idx += NTHR) {
+      const int row = idx / (BN / 8), cv = idx % (BN / 8);
+      float v[8];
+      const f32x4 lo = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8);
+      const f32x4 hi = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+      if (part_id >= 0) {
+        store8(g.partial + (int64_t)part_id * (BM * BN) + (half * WM + row) * BN + cv * 8, v);
+      } else {
+        const int64_t m = m0 + half * WM + row, n = n0 + cv * 8;
+        if (m < g.M && n < g.N) epilogue8(g, m, n, v);
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // Sum the `split` fp32 partial tiles of each tail tile in a fixed order and run the epilogue.
 template <int BM, int BN>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g) {
@@ -468,6 +696,26 @@ int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return MTNLG_HIP_ERROR;
     attr_set = true;
+  }
+  // Aligned problems on the default tile shape take the streaming kernel (all operands by DMA).
+  if constexpr (BM == 256 && BN == 256 && WGM == 2 && WGN == 4 && !KTAIL) {
+    if (g.M % 256 == 0 && g.N % 256 == 0) {
+      constexpr int stream_smem = 5 * 256 * BK * 2;
+      static bool stream_attr_set = false;
+      if (!stream_attr_set) {
+        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<WGN, AT, BT>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess)
+          return MTNLG_HIP_ERROR;
+        stream_attr_set = true;
+      }
+      gemm_stream_kernel<WGN, AT, BT><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
+      MTNLG_TRY(check_launch());
+      if (split) {
+        splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
+        MTNLG_TRY(check_launch());
+      }
+      return MTNLG_OK;
+    }
   }
   gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL><<<dim3(grid), 64 * WGM * WGN, smem, st>>>(g);
   MTNLG_TRY(check_launch());
