@@ -1,27 +1,30 @@
-// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
+// bf16 GEMM on the gfx950 matrix cores, fp32 accumulate:  C[M,N] = op(A) * op(B).
 //
-//   C[M,N] = op(A) * op(B)   with both operands brought into LDS as [row][k] tiles
-//   ("row" = m for A, n for B; 64 k per tile = 128 bytes per row), whatever their
-//   layout in memory:
-//     K-contiguous operand (x in x W^T, W in x W^T, dY in dY W): 16-byte global loads
-//       land in LDS unchanged;
-//     row-contiguous operand (W in dY W, dY and X in dY^T X): each thread loads an
-//       8(k) x 8(row) block with 16-byte loads along the row axis, transposes it in
-//       registers and writes 16-byte k-runs.
-//   Inside a tile, the 16-byte chunk c of row r sits at chunk position
-//   c ^ (r & 7) ^ ((r >> 3) & 7), which keeps both kinds of LDS writes and the
-//   MFMA operand reads (32 rows x one chunk per half-wave) free of bank conflicts.
+// Two kernels share the tile numbering, the split-K tail and the epilogue:
 //
-// Workgroup = WGM x WGN waves (256x256 tile on 2 x 4 waves by default, 128x128 on 2 x 2
-// for small problems); wave tile built from 32x32 MFMA blocks; K advances 64 at a time
-// through two LDS stages (global loads for slab i+1 are in flight while slab i is
-// multiplied), with the LDS traffic interleaved between the MFMAs by scheduling hints.
-// Workgroups are numbered so that the 8 XCDs (workgroup id mod 8) each own a
-// contiguous run of column-major tiles: neighbours in an XCD's L2 share B panels.
+//  * gemm_stream_kernel (aligned problems: M, N multiples of 256, K of 64 -- every GEMM of the
+//    MT-NLG slice): 256x256 tile on 2 x 4 waves, v_mfma_f32_16x16x32_bf16, both operands moved
+//    global -> LDS by DMA through a ring of 2 + 3 stages with the loads spread over the slab,
+//    transposing LDS reads for row-contiguous operands.  Described at its definition.
 //
-// Requirements: K % 8 == 0 and N % 8 == 0; a row-contiguous A also needs M % 8 == 0
-// (16-byte accesses never straddle an edge).  Other edges are handled by clamped
-// loads and masked stores.
+//  * gemm_bf16_kernel (everything else: ragged edges, K tails, small problems):
+//    v_mfma_f32_32x32x16_bf16, both operands brought into LDS as [row][k] tiles ("row" = m for
+//    A, n for B; 64 k per tile = 128 bytes per row), whatever their layout in memory:
+//      K-contiguous operand (x in x W^T, W in x W^T, dY in dY W): 16-byte global loads land in
+//        LDS unchanged (by DMA when K has no tail);
+//      row-contiguous operand (W in dY W, dY and X in dY^T X): each thread loads an 8(k) x 8(row)
+//        block with 16-byte loads along the row axis, transposes it in registers and writes
+//        16-byte k-runs.
+//    Inside a tile, the 16-byte chunk c of row r sits at chunk position
+//    c ^ (r & 7) ^ ((r >> 3) & 7), which keeps both kinds of LDS writes and the MFMA operand
+//    reads free of bank conflicts.  Workgroup = WGM x WGN waves (256x256 tile on 2 x 4 waves by
+//    default, 128x128 on 2 x 2 for small problems); K advances 64 at a time through two LDS
+//    stages, with the LDS traffic interleaved between the MFMAs by scheduling hints.
+//    Requirements: K % 8 == 0 and N % 8 == 0; a row-contiguous A also needs M % 8 == 0 (16-byte
+//    accesses never straddle an edge).  Other edges are handled by clamped loads and masked stores.
+//
+// Workgroups are numbered so that the 8 XCDs (workgroup id mod 8) each own a contiguous run of
+// column-major tiles: neighbours in an XCD's L2 share A and B panels.
 #include <stdlib.h>
 
 #include "common.h"
@@ -417,24 +420,26 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 
 // =======================================================================================
 // Streaming kernel: 256x256 tile, BK = 64, both operands brought global -> LDS by DMA
-// (buffer_load ... lds), no register staging, no LDS store instructions.
+// (buffer_load ... lds), no register staging, no LDS store instructions; MFMA 16x16x32.
 //   A lives in a ring of two 32 KB stages, B in a ring of three (B is the operand that comes
 //   from HBM for the first time: the weights); the DMA instructions of a slab are spread over
-//   the k-steps (two or four per k-step and wave) so that the texture path never sees a burst.
+//   the four phases of a slab (two per phase and wave) so that the texture path never sees a burst.
 //   K-contiguous operand: stage = [256 rows][128 B], 16-byte chunk c of row r at chunk position
 //     c ^ (r & 7) ^ ((r >> 3) & 7); MFMA fragments are 16-byte LDS reads.
-//   Row-contiguous operand ([k][row] in memory): stage = [64 k][512 B] as in memory, 64-byte
-//     granule g of k-row k at granule position g ^ (k & 3); MFMA fragments are two transposing
-//     8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads 4 k-rows x 16 rows and
-//     every lane receives the 4 k values of its own row).
-//   One workgroup barrier per slab, placed before the last k-step (whose fragments are already in
-//   registers) so that the first fragment reads of the next slab hide behind a k-step of MFMAs.
+//   Row-contiguous operand ([k][row] in memory): stage = [64 k][512 B] as in memory, with the
+//     16-byte unit u of k-row k at unit position (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
+//     MFMA fragments are two transposing 8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads
+//     4 k-rows x 16 rows and every lane receives the 4 k values of its own row).
+//   A slab is four phases of 16 MFMAs: (k-step 0, rows 0-63 of the wave tile), (0, rows 64-127),
+//   (1, rows 0-63), (1, rows 64-127); each phase loads the fragments of the next one.  The one
+//   workgroup barrier per slab sits before the last phase (whose fragments are already in
+//   registers) so that the first fragment reads of the next slab hide behind a phase of MFMAs.
 //   Aligned problems only: M, N multiples of 256, K of 64.
-template <int NWN, bool AT, bool BT>
-__global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
+template <bool AT, bool BT>
+__global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int BM = 256, BN = 256, WGM = 2, WGN = NWN, NWAVES = WGM * WGN, NTHR = 64 * NWAVES;
-  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32, KS = BK / 16;
+  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NWAVES = WGM * WGN, NTHR = 64 * NWAVES;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 16, TN = WN / 16, HM = TM / 2;
   constexpr int STAGE = 256 * BK * 2, A_RING = 2 * STAGE, B_RING = 3 * STAGE;
   constexpr int NI = 32 / NWAVES;   // DMA instructions per wave per operand and slab
   const int nk_all = (int)(g.K / BK);
@@ -459,24 +464,21 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
 
   // DMA addressing.  Wave w issues instructions q = NI w .. NI w + NI - 1 of each operand; instruction
   // q fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l the 16 bytes at 16 l.
+  auto dma_offset = [&](int q, int64_t ld, bool transposed) -> uint32_t {
+    if (!transposed) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
+      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
+      return (uint32_t)(row * ld * 2 + c * 16);
+    } else {             // k-rows 2q, 2q+1, lane l: k = 2q + l/32, unit position l%32
+      const int k = 2 * q + (lane >> 5), p = lane & 31;
+      const int u = (((p >> 2) ^ (k & 3)) << 2) | ((p & 3) ^ ((k >> 2) & 2));
+      return (uint32_t)(k * ld * 2 + u * 16);
+    }
+  };
   uint32_t a_off[NI], b_off[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int q = wave * NI + i;
-    if constexpr (!AT) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
-      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
-      a_off[i] = (uint32_t)(row * g.lda * 2 + c * 16);
-    } else {               // k-rows 2q, 2q+1, lane l: k = 2q + l/32, 16-byte unit l%32
-      const int k = 2 * q + (lane >> 5), u = lane & 31;
-      a_off[i] = (uint32_t)(k * g.lda * 2 + ((((u >> 2) ^ (k & 3)) << 2) | (u & 3)) * 16);
-    }
-    if constexpr (!BT) {
-      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
-      b_off[i] = (uint32_t)(row * g.ldb * 2 + c * 16);
-    } else {
-      const int k = 2 * q + (lane >> 5), u = lane & 31;
-      b_off[i] = (uint32_t)(k * g.ldb * 2 + ((((u >> 2) ^ (k & 3)) << 2) | (u & 3)) * 16);
-    }
+    a_off[i] = dma_offset(wave * NI + i, g.lda, AT);
+    b_off[i] = dma_offset(wave * NI + i, g.ldb, BT);
   }
   auto issue = [&](const bf16 *base, const uint32_t(&off)[NI], char *stage, int i0, int i1) {
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
@@ -487,57 +489,55 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16,
                                                  (int)off[i], 0, 0, 0);
   };
-  // slab at k0 (elements): where the operand's tile starts
   auto a_at = [&](int64_t k0) { return AT ? Abase + k0 * g.lda : Abase + k0; };
   auto b_at = [&](int64_t k0) { return BT ? Bbase + k0 * g.ldb : Bbase + k0; };
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
 
-  // fragment of the 32-row block starting at row r0 for k-step kk
+  // MFMA 16x16x32 operand of the 16-row block at r0 for k-step kk (32 k): lane l holds row
+  // r0 + l%16, k = 32 kk + 8 (l/16) .. + 7
   auto frag = [&](const char *stage, int r0, int kk, bool transposed) -> bf16x8 {
     if (!transposed) {
-      const int row = r0 + (lane & 31);
-      return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + swz(row, kk * 2 + (lane >> 5)));
+      const int row = r0 + (lane & 15);
+      return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + swz(row, kk * 4 + (lane >> 4)));
     } else {
-      // lane = 16 grp + L: as address supplier it covers k-row kbase + L/4, rows nb + 4 (L%4) .. +3
+      // as address supplier lane 16 grp + L covers k-row kbase + L/4, rows r0 + 4 (L%4) .. + 3
       const int grp = lane >> 4, L = lane & 15;
-      const int nb = r0 + 16 * (grp & 1) + 4 * (L & 3);
-      const int kbase = 16 * kk + 8 * (grp >> 1) + (L >> 2);
-      i16x4 lo, hi;
-      {
-        const int k = kbase;
-        const char *p = stage + k * 512 + ((((nb >> 5) ^ (k & 3)) << 6) | ((nb & 31) << 1));
-        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
-      }
-      {
-        const int k = kbase + 4;
-        const char *p = stage + k * 512 + ((((nb >> 5) ^ (k & 3)) << 6) | ((nb & 31) << 1));
-        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
-      }
+      const int nb = r0 + 4 * (L & 3);
+      const int kbase = 32 * kk + 8 * grp + (L >> 2);
+      auto addr = [&](int k) {
+        const int u = nb >> 3;                                    // 16-byte unit of the row
+        const int p = (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
+        return stage + k * 512 + p * 16 + (nb & 7) * 2;
+      };
+      const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)addr(kbase));
+      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)addr(kbase + 4));
       i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8, v);
     }
   };
-  bf16x8 af[2][TM], bfr[2][TN];
-  auto read_frags = [&](const char *abuf, const char *bbuf, int kk, bf16x8(&fa)[TM], bf16x8(&fb)[TN]) {
+  bf16x8 af[2][HM], bfr[2][TN];   // A: one buffer per half of the wave tile; B: one per k-step parity
+  auto read_a = [&](const char *abuf, int kk, int h) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[i] = frag(abuf, wm * WM + i * 32, kk, AT);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb[j] = frag(bbuf, wn * WN + j * 32, kk, BT);
+    for (int i = 0; i < HM; ++i) af[h][i] = frag(abuf, wm * WM + (h * HM + i) * 16, kk, AT);
   };
-  auto mfma_rows = [&](int buf) {
+  auto read_b = [&](const char *bbuf, int kk) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j) bfr[kk & 1][j] = frag(bbuf, wn * WN + j * 16, kk, BT);
+  };
+  auto mfma_phase = [&](int kk, int h) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
-      }
+    for (int i = 0; i < HM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[h * HM + i][j] =
+            __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[h][i], bfr[kk & 1][j], acc[h * HM + i][j], 0, 0, 0);
   };
 
   const int nk = slab1 - slab0;
@@ -548,40 +548,46 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
   issue(b_at(slab_k(0)), b_off, bring, 0, NI);
   issue(b_at(slab_k(1)), b_off, bring + STAGE, 0, NI);
   issue(a_at(slab_k(1)), a_off, aring + STAGE, 0, NI / 2);
-  if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // A 0, B 0 landed
-  else asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
-  read_frags(aring, bring, 0, af[0], bfr[0]);
+  asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // A 0, B 0 landed
+  read_a(aring, 0, 0);
+  read_b(bring, 0);
 
+  constexpr int RA = (AT ? 2 : 1) * HM, RB = (BT ? 2 : 1) * TN;   // LDS read instructions of an A half / of B
   int a_cur = 0, b_cur = 0;   // ring offsets of slab `it`
   for (int it = 0; it < nk; ++it) {
     const int a_nxt = a_cur ^ STAGE;
     const int b_nxt = b_cur + STAGE >= B_RING ? b_cur + STAGE - B_RING : b_cur + STAGE;
     const int b_nn = b_nxt + STAGE >= B_RING ? b_nxt + STAGE - B_RING : b_nxt + STAGE;
-    // k-step 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
-    // k-steps 1, 2: B slab it+2 into the ring stage that held slab it-1
-    // k-step 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
+    // phase 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
+    // phases 1, 2: B slab it+2 into the ring stage that held slab it-1
+    // phase 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      // The two waves of a SIMD take turns on the matrix pipe one k-step at a time: the wave that
+    for (int ph = 0; ph < 4; ++ph) {
+      const int kk = ph >> 1, h = ph & 1;
+      // The two waves of a SIMD take turns on the matrix pipe one phase at a time: the wave that
       // is behind (counted from the barrier) has the higher issue priority.
-      if (kk == 0) __builtin_amdgcn_s_setprio(2);
-      else if (kk == 1) __builtin_amdgcn_s_setprio(1);
-      else if (kk == 2) __builtin_amdgcn_s_setprio(0);
-      if (kk == KS - 1) {
+      if (ph == 0) __builtin_amdgcn_s_setprio(2);
+      else if (ph == 1) __builtin_amdgcn_s_setprio(1);
+      else if (ph == 2) __builtin_amdgcn_s_setprio(0);
+      if (ph == 3) {
         // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
-        if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_s_setprio(3);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(aring + a_nxt, bring + b_nxt, 0, af[0], bfr[0]);
+        read_a(aring + a_nxt, 0, 0);
+        read_b(bring + b_nxt, 0);
+      } else if (h == 0) {
+        read_a(aring + a_cur, kk, 1);
       } else {
-        read_frags(aring + a_cur, bring + b_cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+        read_a(aring + a_cur, kk + 1, 0);
+        read_b(bring + b_cur, kk + 1);
       }
-      if (kk == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NI / 2, NI);
-      else if (kk < KS - 1) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (kk - 1) * (NI / 2), kk * (NI / 2));
+      if (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NI / 2, NI);
+      else if (ph < 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (ph - 1) * (NI / 2), ph * (NI / 2));
       else issue(a_at(slab_k(it + 2)), a_off, aring + a_cur, 0, NI / 2);
-      mfma_rows(kk & 1);
-      stream_sched<TM * TN, (AT ? 2 : 1) * TM + (BT ? 2 : 1) * TN, NI / 2>();
+      mfma_phase(kk, h);
+      if (h == 0) stream_sched<HM * TN, RA, NI / 2>();
+      else stream_sched<HM * TN, RA + RB, NI / 2>();
       __builtin_amdgcn_sched_barrier(0);
     }
     a_cur = a_nxt;
@@ -590,6 +596,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   __builtin_amdgcn_s_setprio(0);
 
+  // Epilogue through LDS, one wave-row (wm) of the tile at a time (element e of lane l of block
+  // (i, j) is row 16 i + 4 (l / 16) + e, column 16 j + l % 16 of the wave tile).
   float *img = reinterpret_cast<float *>(smem);
 #pragma unroll
   for (int half = 0; half < WGM; ++half) {
@@ -599,9 +607,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int row = i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            const int col = wn * WN + j * 32 + (lane & 31);
+          for (int e = 0; e < 4; ++e) {
+            const int row = i * 16 + 4 * (lane >> 4) + e;
+            const int col = wn * WN + j * 16 + (lane & 15);
             img[row * BN + col] = acc[i][j][e];
           }
     }
@@ -703,12 +711,12 @@ int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
       constexpr int stream_smem = 5 * 256 * BK * 2;
       static bool stream_attr_set = false;
       if (!stream_attr_set) {
-        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<WGN, AT, BT>,
+        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess)
           return MTNLG_HIP_ERROR;
         stream_attr_set = true;
       }
-      gemm_stream_kernel<WGN, AT, BT><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
+      gemm_stream_kernel<AT, BT><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
       MTNLG_TRY(check_launch());
       if (split) {
         splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
