@@ -781,8 +781,16 @@ size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   return plan_split(tiles256, (int)((K + BK - 1) / BK), 256, 256, 0).workspace;
 }
 
+bool gemm_mfma_streams(int64_t M, int64_t N, int64_t K) {
+  if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % BK) return false;
+  // same choice as pick_tile: small problems take 128x128 tiles
+  const int64_t tiles256 = (M / 256) * (N / 256);
+  return tiles256 >= 160 || plan_split(tiles256, (int)(K / BK), 256, 256, ~(size_t)0).tail > 0;
+}
+
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
-                   const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes, hipStream_t stream) {
+                   const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes, hipStream_t stream,
+                   int prof_class) {
   if (K % 8 || N % 8) return MTNLG_UNSUPPORTED_SHAPE;
   const bool at = layout == MTNLG_GEMM_TN, bt = layout != MTNLG_GEMM_NT;
   if ((at && (M % 8 || M < 8)) || (bt && (N % 8 || N < 8))) return MTNLG_UNSUPPORTED_SHAPE;
@@ -795,7 +803,7 @@ int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, c
   g.ea = EpiArgs{bias, aux, epi};
   g.tiles_m = g.tiles_n = g.per_xcd = 0;
   g.whole_tiles = 0; g.split = 1; g.part_slabs = 0; g.partial = nullptr;
-  LaunchScope scope(MTNLG_K_GEMM_NT + layout, stream);
+  LaunchScope scope(prof_class >= 0 ? prof_class : MTNLG_K_GEMM_NT + layout, stream);
   if (!at && !bt) return pick_tile<false, false>(g, ws, ws_bytes, stream);
   if (!at && bt) return pick_tile<false, true>(g, ws, ws_bytes, stream);
   return pick_tile<true, true>(g, ws, ws_bytes, stream);

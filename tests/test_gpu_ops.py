@@ -209,3 +209,17 @@ def test_gelu_colsum_bias_residual(dtype):
     assert_close(out, to_np(res) + to_np(part) + to_np(bias), tol, "bias_residual")
     M.mtnlg_bias_residual(dev(res), dev(part), None, out)
     assert_close(out, to_np(res) + to_np(part), tol, "residual")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("R,C", [(64, 64), (128, 320), (2048, 7680), (192, 20480)])
+def test_transpose_is_exact(R, C):
+    g = torch.Generator(device="cuda").manual_seed(R + C)
+    a = torch.randn((R, C), generator=g, device="cuda").bfloat16()
+    out = torch.full((C, R), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_transpose(a, out)
+    torch.cuda.synchronize()
+    # a transpose moves bytes: compare bit patterns with the strided view
+    assert torch.equal(out.view(torch.int16), a.t().contiguous().view(torch.int16))
+    with pytest.raises(M.MtnlgError):
+        M.mtnlg_transpose(a[:, :C - 8].contiguous(), torch.empty((C - 8, R), dtype=torch.bfloat16, device="cuda"))
