@@ -536,8 +536,8 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     for (int i = 0; i < HM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[h * HM + i][j] =
-            __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[h][i], bfr[kk & 1][j], acc[h * HM + i][j], 0, 0, 0);
+        acc[h * HM + i][j] =   // B fragment first: the block comes out transposed, see the epilogue
+            __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk & 1][j], af[h][i], acc[h * HM + i][j], 0, 0, 0);
   };
 
   const int nk = slab1 - slab0;
@@ -596,39 +596,40 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   __builtin_amdgcn_s_setprio(0);
 
-  // Epilogue through LDS, one wave-row (wm) of the tile at a time (element e of lane l of block
-  // (i, j) is row 16 i + 4 (l / 16) + e, column 16 j + l % 16 of the wave tile).
-  float *img = reinterpret_cast<float *>(smem);
+  // Epilogue, wave by wave with no workgroup barrier.  The MFMAs took the B fragment as their first
+  // operand, so block (i, j) of the wave tile sits transposed in the registers: lane l holds row
+  // 16 i + l % 16 and the four consecutive columns 16 j + 4 (l / 16) .. + 3.  Each wave turns its
+  // 128 x 64 tile, 64 rows at a time, through a private 64 x 68-float LDS patch (16-byte stores,
+  // conflict-free at that pitch) into 8-column row segments, so that every global access is 16
+  // bytes of a row and a wave instruction covers whole 128-byte lines.
+  {
+    constexpr int PITCH = WN + 4;
+    float *patch = reinterpret_cast<float *>(smem) + wave * (64 * PITCH);
 #pragma unroll
-  for (int half = 0; half < WGM; ++half) {
-    if (wm == half) {
+    for (int p = 0; p < TM / 4; ++p) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
+          *reinterpret_cast<f32x4 *>(patch + ((lane & 15) + i * 16) * PITCH + j * 16 + 4 * (lane >> 4)) = acc[p * 4 + i][j];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int row = i * 16 + 4 * (lane >> 4) + e;
-            const int col = wn * WN + j * 16 + (lane & 15);
-            img[row * BN + col] = acc[i][j][e];
-          }
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < WM * (BN / 8); idx += NTHR) {
-      const int row = idx / (BN / 8), cv = idx % (BN / 8);
-      float v[8];
-      const f32x4 lo = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8);
-      const f32x4 hi = *reinterpret_cast<const f32x4 *>(img + row * BN + cv * 8 + 4);
+      for (int t = 0; t < 8; ++t) {
+        const int row = t * 8 + (lane >> 3), cv = lane & 7;   // 8 rows x 8 segments per instruction
+        float v[8];
+        const f32x4 lo = *reinterpret_cast<const f32x4 *>(patch + row * PITCH + cv * 8);
+        const f32x4 hi = *reinterpret_cast<const f32x4 *>(patch + row * PITCH + cv * 8 + 4);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
-      if (part_id >= 0) {
-        store8(g.partial + (int64_t)part_id * (BM * BN) + (half * WM + row) * BN + cv * 8, v);
-      } else {
-        const int64_t m = m0 + half * WM + row, n = n0 + cv * 8;
-        if (m < g.M && n < g.N) epilogue8(g, m, n, v);
+        for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+        const int trow = wm * WM + p * 64 + row, tcol = wn * WN + cv * 8;   // position in the 256 x 256 tile
+        if (part_id >= 0) {  // K-part of a tail tile: raw fp32 partial, summed by splitk_reduce_kernel
+          store8(g.partial + (int64_t)part_id * (BM * BN) + trow * BN + tcol, v);
+        } else {
+          epilogue8(g, m0 + trow, n0 + tcol, v);
+        }
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // patch is rewritten by the next pass
     }
-    __syncthreads();
   }
 }
 
