@@ -438,7 +438,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 template <bool AT, bool BT>
 __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NWAVES = WGM * WGN, NTHR = 64 * NWAVES;
+  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NWAVES = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 16, TN = WN / 16, HM = TM / 2;
   constexpr int STAGE = 256 * BK * 2, A_RING = 2 * STAGE, B_RING = 3 * STAGE;
   constexpr int NI = 32 / NWAVES;   // DMA instructions per wave per operand and slab
