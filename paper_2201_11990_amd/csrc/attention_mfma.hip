@@ -5,23 +5,26 @@
 //   backward with D_t = da_t . a_t :  dP = da v^T,  dS = P o (dP - D),
 //   dq = scale dS k,  dk = scale dS^T q,  dv = P^T da.
 //
-// All three kernels keep "their" rows in registers as MFMA B operands and stream
-// the other side through LDS in 64-row tiles:
-//   forward  : workgroup = 128 queries (32 per wave); K and V tiles streamed.
-//              S^T = K Q^T puts one query per lane (column of the 32x32 MFMA block)
-//              and keys along the accumulator registers, so the softmax statistics
-//              are lane-local and P^T is already in B-operand form for
-//              O^T += V^T P^T.  V is transposed on its way into LDS.
-//   dq       : same geometry; dQ^T += K^T dS^T with K also kept transposed in LDS.
-//              Also emits D_t for the dk/dv kernel.
-//   dk / dv  : workgroup = 128 keys (32 per wave); Q and dO tiles streamed, both in
-//              natural and transposed form;  dV^T += dO^T P,  dK^T += Q^T dS.
-// No atomics: every output element has one owner, results are run-to-run identical.
+// Three kernels, one geometry.  A workgroup of four waves owns 128 rows of one side
+// (queries for forward and dq, keys for dk/dv), 32 per wave, held in registers as MFMA
+// B operands (two groups of 16, one row per lane column); the other side streams through
+// LDS in tiles of 64 rows, brought in by LDS DMA (buffer_load ... lds, no staging
+// registers) three tiles deep, one workgroup barrier per tile.
 //
-// Transposed tiles are [D][64] with the 64 "k" positions of a row permuted (bits 2
-// and 3 of the index swapped inside each group of 16) so that the 8 values a lane
-// needs for one MFMA step -- the ones matching accumulator registers 8t..8t+7 of
-// the producing block -- are one 16-byte LDS read.
+// All products are v_mfma_f32_16x16x32_bf16 with the streamed tile as the A operand, so a
+// product block comes out as C[tile row 4 (lane/16) + i][own row lane%16], i = 0..3:
+//   forward : S^T = K Q^T; the softmax statistics of a query live in the four lanes that
+//             share lane%16; P^T packed to bf16 is directly the B operand of O^T += V^T P^T.
+//   dq      : S^T and dP^T = V dO^T the same way, dQ^T += K^T dS^T.
+//   dk / dv : S = Q K^T, dP = dO V^T with the key on the lane column,
+//             dV^T += dO^T P, dK^T += Q^T dS.
+// The second product of each chain contracts over the tile's rows.  Its A operand is read
+// from the same natural [row][D] tile with the transposing LDS read (ds_read_b64_tr_b16: a
+// 16-lane group reads 4 tile rows x 16 columns, each lane receives the 4 row values of its
+// column); the k slots of that MFMA are ordered to match the accumulator layout of the
+// first product (slot (g, e) of a 32-row step = tile row 4g + e for e < 4, 16 + 4g + e - 4
+// otherwise), so P and dS never leave the registers and nothing is transposed in software.
+// No atomics: every output element has one owner, results are run-to-run identical.
 #include <math.h>
 
 #include "common.h"
@@ -32,210 +35,259 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((address_space(3))) i16x4 *lds_i16x4_ptr;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// chunk position inside a natural [rows][D] tile (row = 2*D bytes)
-template <int D>
-__device__ __forceinline__ int nat_off(int r, int c) {
-  if constexpr ((2 * D) % 128 == 0)
-    return r * (2 * D) + ((c ^ (r & 7)) << 4);
-  else  // 2*D = 64 mod 128 (D = 160): rows alternate between two bank halves
-    return r * (2 * D) + ((c ^ ((r >> 1) & 3)) << 4);
-}
-// chunk position inside a transposed [D][64] tile (row = 128 bytes)
-__device__ __forceinline__ int tr_off(int r, int c) { return r * 128 + ((c ^ (r & 7) ^ ((r >> 3) & 7)) << 4); }
-
-// One 8(rows) x 8(cols) block of a 64-row x D-column bf16 tile per thread.
-template <int D>
-struct Block64 {
-  static constexpr int DB = D / 8;       // column blocks
-  static constexpr int NB = 8 * DB;      // blocks in the tile
-  static_assert(NB <= 256, "one block per thread");
-  i16x8 r[8];
-  // rows row0.. of a matrix with leading dimension ld; rows >= rows_total are clamped
-  __device__ __forceinline__ void fetch(const bf16 *base, int64_t ld, int row0, int rows_total) {
-    if (threadIdx.x < NB) {
-      const int rb = threadIdx.x / DB, db = threadIdx.x % DB;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        int row = row0 + rb * 8 + i;
-        row = row < rows_total ? row : rows_total - 1;
-        r[i] = *reinterpret_cast<const i16x8 *>(base + (int64_t)row * ld + db * 8);
-      }
-    }
-  }
-  __device__ __forceinline__ void stash_natural(char *lds) const {
-    if (threadIdx.x < NB) {
-      const int rb = threadIdx.x / DB, db = threadIdx.x % DB;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<i16x8 *>(lds + nat_off<D>(rb * 8 + i, db)) = r[i];
-    }
-  }
-  __device__ __forceinline__ void stash_transposed(char *lds) const {
-    if (threadIdx.x < NB) {
-      const int rb = threadIdx.x / DB, db = threadIdx.x % DB;
-      const int c0 = 2 * (rb >> 1), half = (rb & 1) * 8;  // 16-group rb/2, element offset 4*(rb&1)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = db * 8 + e;
-        i16x4 lo, hi;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          lo[j] = r[j][e];
-          hi[j] = r[4 + j][e];
-        }
-        *reinterpret_cast<i16x4 *>(lds + tr_off(row, c0) + half) = lo;
-        *reinterpret_cast<i16x4 *>(lds + tr_off(row, c0 + 1) + half) = hi;
-      }
-    }
-  }
-};
-
-template <int D>
-__device__ __forceinline__ bf16x8 frag_nat(const char *lds, int row, int c) {
-  return *reinterpret_cast<const bf16x8 *>(lds + nat_off<D>(row, c));
-}
-__device__ __forceinline__ bf16x8 frag_tr(const char *lds, int row, int c) {
-  return *reinterpret_cast<const bf16x8 *>(lds + tr_off(row, c));
-}
-// accumulator registers 8t..8t+7 of a 32x32 block as a bf16 B operand
-__device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int t) {
-  bf16x8 o;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) o[i] = (bf16)v[8 * t + i];
-  return o;
-}
-// row index inside a 32x32 block of accumulator register e for lane group g
-__device__ __forceinline__ int acc_row(int e, int g) { return 8 * (e >> 2) + 4 * g + (e & 3); }
+#define MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0)
 
 // 2^x on the transcendental unit (v_exp_f32): no denormal fix-up, 2^-inf = 0.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+// A 64-row x D-column bf16 tile in LDS, rows as in memory, the 16-byte units of a row
+// permuted by an XOR that depends on the row so that both kinds of fragment read are free
+// of bank conflicts (checked by enumeration for the three head sizes).
+template <int D>
+struct Tile {
+  static constexpr int UPR = D / 8;        // 16-byte units per row
+  static constexpr int BYTES = 64 * D * 2;
+  static constexpr int NI = D / 32;        // DMA instructions per wave and tile (16 rows)
+  static __device__ __forceinline__ int mask(int row) {
+    if constexpr (D == 160) return ((row >> 2) & 1) * 2 + ((row >> 3) & 1);
+    else if constexpr (D == 128) return ((row & 7) << 1) | ((row >> 3) & 1);
+    else return (((row >> 1) & 3) << 1) | ((row >> 3) & 1);
+  }
+  static __device__ __forceinline__ int off(int row, int u) { return (row * UPR + (u ^ mask(row))) * 16; }
+
+  // Wave `wave` brings rows 16 wave .. 16 wave + 15 of the tile whose first row is row0 of the
+  // matrix behind rs (row pitch ld_bytes); rows past the end repeat the last row.  A DMA
+  // instruction fills 1024 consecutive LDS bytes, lane l the 16 bytes at 16 l.
+  static __device__ __forceinline__ void dma(dma_rsrc_t rs, int row0, int rows_total, uint32_t ld_bytes,
+                                             char *stage, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int p = i * 64 + lane;
+      const int r = 16 * wave + p / UPR, u = (p % UPR) ^ mask(16 * wave + p / UPR);
+      int gr = row0 + r;
+      gr = gr < rows_total ? gr : rows_total - 1;
+      dma16(rs, stage + (wave * NI + i) * 1024, gr * ld_bytes + u * 16);
+    }
+  }
+  // Byte offsets of a lane's fragment reads inside a tile.  mask() looks at the low four bits of a
+  // row only, so a block of 16 rows further down is a constant distance away.
+  struct Lane {
+    int nat[D / 32];   // row lane%16, 16-byte unit 4 kk + lane/16
+    int tr[D / 16];    // as address supplier of a transposing read: row 4 (lane/16) + L/4, columns 16 cblk + 4 (L%4) .. + 3, L = lane%16
+    __device__ __forceinline__ explicit Lane(int lane) {
+      const int g = lane >> 4, L = lane & 15;
+#pragma unroll
+      for (int kk = 0; kk < D / 32; ++kk) nat[kk] = off(L, 4 * kk + g);
+#pragma unroll
+      for (int cb = 0; cb < D / 16; ++cb) {
+        const int col = cb * 16 + 4 * (L & 3);
+        tr[cb] = off(4 * g + (L >> 2), col >> 3) + (col & 7) * 2;
+      }
+    }
+  };
+  static constexpr int ROWS16 = 16 * UPR * 16;   // bytes of 16 tile rows
+  // A operand contracting over columns: lane l holds row 16 blk + l%16, columns 32 kk + 8 (l/16) .. + 7
+  static __device__ __forceinline__ bf16x8 nat(const char *t, const Lane &ln, int blk, int kk) {
+    return *reinterpret_cast<const bf16x8 *>(t + ln.nat[kk] + blk * ROWS16);
+  }
+  // A operand contracting over tile rows 32 ks .. 32 ks + 31: lane l holds column 16 cblk + l%16 and,
+  // with g = l/16, tile rows 32 ks + 4 g .. + 3 (elements 0-3) and 32 ks + 16 + 4 g .. + 3 (4-7).
+  static __device__ __forceinline__ bf16x8 tr(const char *t, const Lane &ln, int cblk, int ks) {
+    const char *p = t + ln.tr[cblk] + 2 * ks * ROWS16;
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)p);
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p + ROWS16));
+    const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+// two accumulator blocks (tile rows 32 ks + 4g + i and 32 ks + 16 + 4g + i) as the bf16 B operand
+__device__ __forceinline__ bf16x8 pack2(const f32x4 &lo, const f32x4 &hi) {
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[i] = (bf16)lo[i];
+    o[4 + i] = (bf16)hi[i];
+  }
+  return o;
+}
+
+// wait until at most N of this wave's memory operations are outstanding, then the workgroup barrier
+template <int N>
+__device__ __forceinline__ void wait_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// The value is needed "now": makes the compiler wait for the global load behind v here, before the
+// main loop, rather than at the first use inside it -- a wait for ordinary loads inside the loop
+// would also drain the DMAs in flight, which the compiler does not know about.
+template <typename V>
+__device__ __forceinline__ void arrive(V &v) {
+  asm volatile("" : "+v"(v));
+}
+
+// sum / maximum over the four lanes that share lane % 16
+__device__ __forceinline__ float quad_sum(float v) {
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
+}
+__device__ __forceinline__ float quad_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
+}
 
 // ------------------------------------------------------------------ forward
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
                                                        bf16 *__restrict__ a, float *__restrict__ lse) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int KK = D / 16, DBK = D / 32, TILE = 64 * D * 2, STAGE = 2 * TILE;
-  const int qt = gridDim.x - 1 - blockIdx.x, j = blockIdx.y, bi = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  using T = Tile<D>;
+  constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
+  const int qt = gridDim.x - 1 - blockIdx.x, j = blockIdx.y, bi = blockIdx.z;   // long rows first
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
   const int q0 = qt * 128, qw = q0 + wave * 32;
-  const int q = qw + (lane & 31), qc = q < s ? q : s - 1;
   const float c = scale * kLog2e;
+  const typename T::Lane ln(lane);
 
-  bf16x8 qf[KK];
+  int qc[2];
+  bf16x8 qf[2][KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk)
-    qf[kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)qc * ld + (2 * kk + g) * 8);
+  for (int qg = 0; qg < 2; ++qg) {
+    const int q = qw + 16 * qg + lr;
+    qc[qg] = q < s ? q : s - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      qf[qg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)qc[qg] * ld + 32 * kk + 8 * g);
+  }
+  f32x4 o[2][DB];
+#pragma unroll
+  for (int qg = 0; qg < 2; ++qg)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[qg][db][e] = 0.0f;
+  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};   // l: this lane's share of the row sum
 
-  f32x16 oacc[DBK];
-#pragma unroll
-  for (int db = 0; db < DBK; ++db)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
-  float m = -INFINITY, l = 0.0f;
-
-  int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
+  const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
-  Block64<D> kb, vb;
-  kb.fetch(base + D, ld, 0, s);
-  vb.fetch(base + 2 * D, ld, 0, s);
-  kb.stash_natural(smem);
-  vb.stash_transposed(smem + TILE);
-  __syncthreads();
-
+  const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
+  auto issue = [&](int t, int st) {   // tile t (clamped to the last one) into ring stage st
+    const int tt = t < ntiles ? t : ntiles - 1;
+    T::dma(rk, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE, wave, lane);
+    T::dma(rv, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE + T::BYTES, wave, lane);
+  };
+  issue(0, 0);
+  issue(1, 1);
+#pragma unroll
+  for (int qg = 0; qg < 2; ++qg)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) arrive(qf[qg][kk]);
+  int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
-    const char *Kt = smem + (it & 1) * STAGE, *Vt = Kt + TILE;
-    char *nxt = smem + ((it + 1) & 1) * STAGE;
-    const bool more = it + 1 < ntiles;
+    wait_and_barrier<2 * T::NI>();   // tile it landed everywhere, tile it-1 no longer read
+    const int nn = cur == 0 ? 2 : cur - 1;
+    issue(it + 2, nn);
+    const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (more) {
-      kb.fetch(base + D, ld, kv0 + 64, s);
-      vb.fetch(base + 2 * D, ld, kv0 + 64, s);
-    }
     if (kv0 <= qw + 31) {  // wave-uniform: some (query, key) pair of this wave is unmasked
-      f32x16 sacc[2];
+      f32x4 sc[2][4];
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[blk][e] = 0.0f;
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sc[qg][kb][e] = 0.0f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-          sacc[blk] = MFMA(frag_nat<D>(Kt, blk * 32 + (lane & 31), 2 * kk + g), qf[kk], sacc[blk]);
-      // m tracks the running maximum of the raw scores; exponents are taken in base 2
-      // with the scale folded in: p = 2^(s*c - m*c).
+        for (int kb = 0; kb < 4; ++kb) {
+          const bf16x8 kfr = T::nat(Kt, ln, kb, kk);
+#pragma unroll
+          for (int qg = 0; qg < 2; ++qg) sc[qg][kb] = MFMA16(kfr, qf[qg][kk], sc[qg][kb]);
+        }
+      // element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       if (kv0 + 63 > qw) {  // wave-uniform: this tile crosses the diagonal for some row
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
+        for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (kv0 + blk * 32 + acc_row(e, g) > qc) sacc[blk][e] = -INFINITY;
+          for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (kv0 + 16 * kb + 4 * g + e > qc[qg]) sc[qg][kb][e] = -INFINITY;
       }
-      float mx = -INFINITY;
+      // m tracks the running maximum of the raw scores; exponents are taken in base 2 with the
+      // scale folded in: p = 2^(s c - m c).
+      float alpha[2];
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      for (int qg = 0; qg < 2; ++qg) {
+        float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[blk][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);  // finite from the first tile on (key 0 is never masked)
-      const float mc = m_new * c;
-      float rs = 0.0f;
+        for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+          for (int e = 0; e < 4; ++e) mx = fmaxf(mx, sc[qg][kb][e]);
+        mx = quad_max(mx);
+        const float m_new = fmaxf(m[qg], mx);  // finite from the first tile on (key 0 is never masked)
+        const float mc = m_new * c;
+        float rs = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = fast_exp2(fmaf(sacc[blk][e], c, -mc));
-          sacc[blk][e] = p;
-          rs += p;
-        }
-      rs += __shfl_xor(rs, 32, 64);
-      const float alpha = fast_exp2((m - m_new) * c);
-      l = l * alpha + rs;
-      if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {  // some row's maximum moved: rescale O
+        for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int db = 0; db < DBK; ++db)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+          for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp2(fmaf(sc[qg][kb][e], c, -mc));
+            sc[qg][kb][e] = p;
+            rs += p;
+          }
+        alpha[qg] = fast_exp2((m[qg] - m_new) * c);
+        l[qg] = l[qg] * alpha[qg] + rs;
+        m[qg] = m_new;
       }
-      m = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {  // a maximum moved: rescale O
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+        for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 pf = pack8(sacc[blk], t);
+          for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int db = 0; db < DBK; ++db)
-            oacc[db] = MFMA(frag_tr(Vt, db * 32 + (lane & 31), 2 * (2 * blk + t) + g), pf, oacc[db]);
+            for (int e = 0; e < 4; ++e) o[qg][db][e] *= alpha[qg];
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 pf0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]);
+        const bf16x8 pf1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 vfr = T::tr(Vt, ln, db, ks);
+          o[0][db] = MFMA16(vfr, pf0, o[0][db]);
+          o[1][db] = MFMA16(vfr, pf1, o[1][db]);
         }
+      }
     }
-    if (more) {
-      kb.stash_natural(nxt);
-      vb.stash_transposed(nxt + TILE);
-    }
-    __syncthreads();
+    cur = cur == 2 ? 0 : cur + 1;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped look-ahead tiles
 
-  if (q < s) {
-    const float inv = 1.0f / l;
-    bf16 *out = a + ((int64_t)bi * s + q) * ((int64_t)n * D) + (int64_t)j * D;
 #pragma unroll
-    for (int db = 0; db < DBK; ++db)
+  for (int qg = 0; qg < 2; ++qg) {
+    const int q = qw + 16 * qg + lr;
+    const float lsum = quad_sum(l[qg]);
+    if (q < s) {
+      const float inv = 1.0f / lsum;
+      bf16 *out = a + ((int64_t)bi * s + q) * ((int64_t)n * D) + (int64_t)j * D;
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        bf16x4 o;
+      for (int db = 0; db < DB; ++db) {
+        bf16x4 v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[db][4 * e4 + i] * inv);
-        *reinterpret_cast<bf16x4 *>(out + db * 32 + 8 * e4 + 4 * g) = o;
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[qg][db][e] * inv);
+        *reinterpret_cast<bf16x4 *>(out + db * 16 + 4 * g) = v;
       }
-    if (g == 0) lse[((int64_t)bi * n + j) * s + q] = (m * c + log2f(l)) * kLn2;
+      if (g == 0) lse[((int64_t)bi * n + j) * s + q] = (m[qg] * c + log2f(lsum)) * kLn2;
+    }
   }
 }
 
@@ -246,109 +298,134 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
                                                           const bf16 *__restrict__ da, bf16 *__restrict__ dqkv,
                                                           float *__restrict__ Dvec) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int KK = D / 16, DBK = D / 32, TILE = 64 * D * 2;
+  using T = Tile<D>;
+  constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
   const int qt = gridDim.x - 1 - blockIdx.x, j = blockIdx.y, bi = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
   const int q0 = qt * 128, qw = q0 + wave * 32;
-  const int q = qw + (lane & 31), qc = q < s ? q : s - 1;
   const float c = scale * kLog2e;
+  const typename T::Lane ln(lane);
 
-  bf16x8 qf[KK], dof[KK];
-  float dsum = 0.0f;
-  {
-    const bf16 *dar = da + ((int64_t)bi * s + qc) * pld + (int64_t)j * D;
-    const bf16 *ar = a + ((int64_t)bi * s + qc) * pld + (int64_t)j * D;
+  int qc[2];
+  bf16x8 qf[2][KK], dof[2][KK];
+  float dsum[2], lse2[2];
+#pragma unroll
+  for (int qg = 0; qg < 2; ++qg) {
+    const int q = qw + 16 * qg + lr;
+    qc[qg] = q < s ? q : s - 1;
+    const bf16 *dar = da + ((int64_t)bi * s + qc[qg]) * pld + (int64_t)j * D;
+    const bf16 *ar = a + ((int64_t)bi * s + qc[qg]) * pld + (int64_t)j * D;
+    float ds = 0.0f;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      qf[kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)qc * ld + (2 * kk + g) * 8);
-      dof[kk] = *reinterpret_cast<const bf16x8 *>(dar + (2 * kk + g) * 8);
-      const bf16x8 av = *reinterpret_cast<const bf16x8 *>(ar + (2 * kk + g) * 8);
+      qf[qg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)qc[qg] * ld + 32 * kk + 8 * g);
+      dof[qg][kk] = *reinterpret_cast<const bf16x8 *>(dar + 32 * kk + 8 * g);
+      const bf16x8 av = *reinterpret_cast<const bf16x8 *>(ar + 32 * kk + 8 * g);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dsum += (float)dof[kk][i] * (float)av[i];
+      for (int i = 0; i < 8; ++i) ds += (float)dof[qg][kk][i] * (float)av[i];
     }
+    dsum[qg] = quad_sum(ds);
+    lse2[qg] = lse[((int64_t)bi * n + j) * s + qc[qg]] * kLog2e;
+    if (q < s && g == 0) Dvec[((int64_t)bi * n + j) * s + q] = dsum[qg];
   }
-  dsum += __shfl_xor(dsum, 32, 64);
-  const float lse2 = lse[((int64_t)bi * n + j) * s + qc] * kLog2e;
-  if (q < s && g == 0) Dvec[((int64_t)bi * n + j) * s + q] = dsum;
 
-  f32x16 dq[DBK];
+  f32x4 dq[2][DB];
 #pragma unroll
-  for (int db = 0; db < DBK; ++db)
+  for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) dq[db][e] = 0.0f;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dq[qg][db][e] = 0.0f;
 
-  int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
+  const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
-  char *Kn = smem, *Vn = smem + TILE, *Kt = smem + 2 * TILE;
-  Block64<D> kb, vb;
-  kb.fetch(base + D, ld, 0, s);
-  vb.fetch(base + 2 * D, ld, 0, s);
-
-  for (int it = 0; it < ntiles; ++it) {
-    const int kv0 = it * 64;
-    __syncthreads();  // previous tile fully consumed
-    kb.stash_natural(Kn);
-    kb.stash_transposed(Kt);
-    vb.stash_natural(Vn);
-    __syncthreads();
-    if (it + 1 < ntiles) {
-      kb.fetch(base + D, ld, kv0 + 64, s);
-      vb.fetch(base + 2 * D, ld, kv0 + 64, s);
+  const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
+  auto issue = [&](int t, int st) {
+    const int tt = t < ntiles ? t : ntiles - 1;
+    T::dma(rk, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE, wave, lane);
+    T::dma(rv, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE + T::BYTES, wave, lane);
+  };
+  issue(0, 0);
+  issue(1, 1);
+#pragma unroll
+  for (int qg = 0; qg < 2; ++qg) {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      arrive(qf[qg][kk]);
+      arrive(dof[qg][kk]);
     }
+    arrive(lse2[qg]);
+    arrive(dsum[qg]);
+  }
+  int cur = 0;
+  for (int it = 0; it < ntiles; ++it) {
+    wait_and_barrier<2 * T::NI>();
+    const int nn = cur == 0 ? 2 : cur - 1;
+    issue(it + 2, nn);
+    const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
+    const int kv0 = it * 64;
     if (kv0 <= qw + 31) {
-      f32x16 sacc[2], pacc[2];
+      f32x4 sc[2][4], pc[2][4];
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[blk][e] = pacc[blk][e] = 0.0f;
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sc[qg][kb][e] = pc[qg][kb][e] = 0.0f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-          sacc[blk] = MFMA(frag_nat<D>(Kn, blk * 32 + (lane & 31), 2 * kk + g), qf[kk], sacc[blk]);
-          pacc[blk] = MFMA(frag_nat<D>(Vn, blk * 32 + (lane & 31), 2 * kk + g), dof[kk], pacc[blk]);
-        }
-      // dS^T = P^T o (dP^T - D)
-      if (kv0 + 63 > qw) {  // wave-uniform: diagonal (or past-the-end keys) in this tile
+        for (int kb = 0; kb < 4; ++kb) {
+          const bf16x8 kfr = T::nat(Kt, ln, kb, kk), vfr = T::nat(Vt, ln, kb, kk);
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int kv = kv0 + blk * 32 + acc_row(e, g);
-            const float p = kv > qc ? 0.0f : fast_exp2(fmaf(sacc[blk][e], c, -lse2));
-            sacc[blk][e] = p * (pacc[blk][e] - dsum);
+          for (int qg = 0; qg < 2; ++qg) {
+            sc[qg][kb] = MFMA16(kfr, qf[qg][kk], sc[qg][kb]);
+            pc[qg][kb] = MFMA16(vfr, dof[qg][kk], pc[qg][kb]);
           }
-      } else {
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            sacc[blk][e] = fast_exp2(fmaf(sacc[blk][e], c, -lse2)) * (pacc[blk][e] - dsum);
-      }
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 df = pack8(sacc[blk], t);
-#pragma unroll
-          for (int db = 0; db < DBK; ++db)
-            dq[db] = MFMA(frag_tr(Kt, db * 32 + (lane & 31), 2 * (2 * blk + t) + g), df, dq[db]);
         }
-    }
-  }
-  if (q < s) {
-    bf16 *out = dqkv + ((int64_t)bi * s + q) * ld + (int64_t)j * 3 * D;
+      // dS^T = P^T o (dP^T - D); element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
+      const bool diag = kv0 + 63 > qw;  // wave-uniform: diagonal (or past-the-end keys) in this tile
 #pragma unroll
-    for (int db = 0; db < DBK; ++db)
+      for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        bf16x4 o;
+        for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (bf16)(dq[db][4 * e4 + i] * scale);
-        *reinterpret_cast<bf16x4 *>(out + db * 32 + 8 * e4 + 4 * g) = o;
+          for (int e = 0; e < 4; ++e) {
+            float p = fast_exp2(fmaf(sc[qg][kb][e], c, -lse2[qg]));
+            if (diag && kv0 + 16 * kb + 4 * g + e > qc[qg]) p = 0.0f;
+            sc[qg][kb][e] = p * (pc[qg][kb][e] - dsum[qg]);
+          }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 df0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]);
+        const bf16x8 df1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 ktr = T::tr(Kt, ln, db, ks);
+          dq[0][db] = MFMA16(ktr, df0, dq[0][db]);
+          dq[1][db] = MFMA16(ktr, df1, dq[1][db]);
+        }
       }
+    }
+    cur = cur == 2 ? 0 : cur + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+#pragma unroll
+  for (int qg = 0; qg < 2; ++qg) {
+    const int q = qw + 16 * qg + lr;
+    if (q < s) {
+      bf16 *out = dqkv + ((int64_t)bi * s + q) * ld + (int64_t)j * 3 * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[qg][db][e] * scale);
+        *reinterpret_cast<bf16x4 *>(out + db * 16 + 4 * g) = v;
+      }
+    }
   }
 }
 
@@ -359,125 +436,146 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
                                                            const float *__restrict__ Dvec,
                                                            const bf16 *__restrict__ da, bf16 *__restrict__ dqkv) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int KK = D / 16, DBK = D / 32, TILE = 64 * D * 2;
-  const int kt = blockIdx.x, j = blockIdx.y, bi = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  using T = Tile<D>;
+  constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES + 512;   // Q tile, dO tile, lse[64], D[64]
+  const int kt = blockIdx.x, j = blockIdx.y, bi = blockIdx.z;   // long columns first
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
   const bf16 *dab = da + (int64_t)bi * s * pld + (int64_t)j * D;
   const int k0 = kt * 128, kw = k0 + wave * 32;
-  const int key = kw + (lane & 31), keyc = key < s ? key : s - 1;
   const float c = scale * kLog2e;
+  const typename T::Lane ln(lane);
 
-  bf16x8 kf[KK], vf[KK];
+  int key[2];
+  bf16x8 kf[2][KK], vf[2][KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    kf[kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)keyc * ld + D + (2 * kk + g) * 8);
-    vf[kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)keyc * ld + 2 * D + (2 * kk + g) * 8);
+  for (int kg = 0; kg < 2; ++kg) {
+    key[kg] = kw + 16 * kg + lr;
+    const int keyc = key[kg] < s ? key[kg] : s - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)keyc * ld + D + 32 * kk + 8 * g);
+      vf[kg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)keyc * ld + 2 * D + 32 * kk + 8 * g);
+    }
   }
-  f32x16 dk[DBK], dv[DBK];
+  f32x4 dk[2][DB], dv[2][DB];
 #pragma unroll
-  for (int db = 0; db < DBK; ++db)
+  for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dk[kg][db][e] = dv[kg][db][e] = 0.0f;
 
-  char *Qn = smem, *On = smem + TILE, *Qt = smem + 2 * TILE, *Ot = smem + 3 * TILE;
-  float *stat = reinterpret_cast<float *>(smem + 4 * TILE);  // [0..63] lse*log2e, [64..127] D
-  const float *lrow = lse + ((int64_t)bi * n + j) * s, *drow = Dvec + ((int64_t)bi * n + j) * s;
-
-  const int t_first = k0 / 64, t_end = (s + 63) / 64;
-  Block64<D> qb, ob;
-  qb.fetch(base, ld, t_first * 64, s);
-  ob.fetch(dab, pld, t_first * 64, s);
-
-  for (int it = t_first; it < t_end; ++it) {
-    const int q0 = it * 64;
-    __syncthreads();
-    qb.stash_natural(Qn);
-    qb.stash_transposed(Qt);
-    ob.stash_natural(On);
-    ob.stash_transposed(Ot);
-    if (threadIdx.x < 64) {
-      int qq = q0 + threadIdx.x;
-      qq = qq < s ? qq : s - 1;
-      stat[threadIdx.x] = lrow[qq] * kLog2e;
-      stat[64 + threadIdx.x] = drow[qq];
+  const int t_first = k0 / 64, ntiles = (s + 63) / 64 - t_first;
+  const dma_rsrc_t rq = dma_rsrc(base), ro = dma_rsrc(dab);
+  // even waves bring the tile's lse values, odd waves its D values (twice each: every wave issues
+  // the same number of memory operations, which the counted waits below rely on)
+  const dma_rsrc_t rstat =
+      dma_rsrc(((wave & 1) ? Dvec : lse) + ((int64_t)bi * n + j) * s);
+  auto issue = [&](int t, int st) {
+    const int tt = t < ntiles ? t : ntiles - 1;
+    const int row0 = (t_first + tt) * 64;
+    char *stage = smem + st * STAGE;
+    T::dma(rq, row0, s, (uint32_t)(ld * 2), stage, wave, lane);
+    T::dma(ro, row0, s, (uint32_t)(pld * 2), stage + T::BYTES, wave, lane);
+    int qq = row0 + lane;
+    qq = qq < s ? qq : s - 1;
+    dma4(rstat, stage + 2 * T::BYTES + (wave & 1) * 256, qq * 4);
+  };
+  issue(0, 0);
+  issue(1, 1);
+#pragma unroll
+  for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      arrive(kf[kg][kk]);
+      arrive(vf[kg][kk]);
     }
-    __syncthreads();
-    if (it + 1 < t_end) {
-      qb.fetch(base, ld, q0 + 64, s);
-      ob.fetch(dab, pld, q0 + 64, s);
-    }
+  int cur = 0;
+  for (int it = 0; it < ntiles; ++it) {
+    wait_and_barrier<2 * T::NI + 1>();
+    const int nn = cur == 0 ? 2 : cur - 1;
+    issue(it + 2, nn);
+    const char *Qt = smem + cur * STAGE, *Ot = Qt + T::BYTES;
+    const float *stat = reinterpret_cast<const float *>(Qt + 2 * T::BYTES);
+    const int q0 = (t_first + it) * 64;
     if (q0 + 63 >= kw) {  // wave-uniform: some query of the tile sees a key of this wave
-      f32x16 sacc[2], pacc[2];
+      f32x4 sc[2][4], pc[2][4];
 #pragma unroll
-      for (int qb2 = 0; qb2 < 2; ++qb2)
+      for (int kg = 0; kg < 2; ++kg)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[qb2][e] = pacc[qb2][e] = 0.0f;
+        for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sc[kg][qb][e] = pc[kg][qb][e] = 0.0f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int qb2 = 0; qb2 < 2; ++qb2) {
-          sacc[qb2] = MFMA(frag_nat<D>(Qn, qb2 * 32 + (lane & 31), 2 * kk + g), kf[kk], sacc[qb2]);
-          pacc[qb2] = MFMA(frag_nat<D>(On, qb2 * 32 + (lane & 31), 2 * kk + g), vf[kk], pacc[qb2]);
-        }
-      // element (register e, lane) is query q0 + 32*qb2 + acc_row(e,g), key = this lane's key
-      if (q0 < kw + 32 || q0 + 63 >= s) {  // wave-uniform: diagonal or past-the-end queries
+        for (int qb = 0; qb < 4; ++qb) {
+          const bf16x8 qfr = T::nat(Qt, ln, qb, kk), ofr = T::nat(Ot, ln, qb, kk);
 #pragma unroll
-        for (int qb2 = 0; qb2 < 2; ++qb2)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int ql = qb2 * 32 + acc_row(e, g);
-            const int qq = q0 + ql;
-            const float p = (qq < key || qq >= s) ? 0.0f : fast_exp2(fmaf(sacc[qb2][e], c, -stat[ql]));
-            sacc[qb2][e] = p;
-            pacc[qb2][e] = p * (pacc[qb2][e] - stat[64 + ql]);
+          for (int kg = 0; kg < 2; ++kg) {
+            sc[kg][qb] = MFMA16(qfr, kf[kg][kk], sc[kg][qb]);
+            pc[kg][qb] = MFMA16(ofr, vf[kg][kk], pc[kg][qb]);
           }
-      } else {
+        }
+      // element (kg, qb, e): query q0 + 16 qb + 4 g + e, key key[kg]
+      const bool edge = q0 < kw + 32 || q0 + 63 >= s;  // wave-uniform: diagonal or past-the-end queries
 #pragma unroll
-        for (int qb2 = 0; qb2 < 2; ++qb2)
+      for (int qb = 0; qb < 4; ++qb) {
+        const f32x4 ls = *reinterpret_cast<const f32x4 *>(stat + 16 * qb + 4 * g);
+        const f32x4 dd = *reinterpret_cast<const f32x4 *>(stat + 64 + 16 * qb + 4 * g);
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int ql = qb2 * 32 + acc_row(e, g);
-            const float p = fast_exp2(fmaf(sacc[qb2][e], c, -stat[ql]));
-            sacc[qb2][e] = p;
-            pacc[qb2][e] = p * (pacc[qb2][e] - stat[64 + ql]);
+        for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int qq = q0 + 16 * qb + 4 * g + e;
+            float p = fast_exp2(fmaf(sc[kg][qb][e], c, -ls[e] * kLog2e));
+            if (edge && (qq < key[kg] || qq >= s)) p = 0.0f;
+            sc[kg][qb][e] = p;
+            pc[kg][qb][e] = p * (pc[kg][qb][e] - dd[e]);
           }
       }
 #pragma unroll
-      for (int qb2 = 0; qb2 < 2; ++qb2)
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 pf0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]), pf1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
+        const bf16x8 df0 = pack2(pc[0][2 * ks], pc[0][2 * ks + 1]), df1 = pack2(pc[1][2 * ks], pc[1][2 * ks + 1]);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 pf = pack8(sacc[qb2], t), df = pack8(pacc[qb2], t);
-#pragma unroll
-          for (int db = 0; db < DBK; ++db) {
-            dv[db] = MFMA(frag_tr(Ot, db * 32 + (lane & 31), 2 * (2 * qb2 + t) + g), pf, dv[db]);
-            dk[db] = MFMA(frag_tr(Qt, db * 32 + (lane & 31), 2 * (2 * qb2 + t) + g), df, dk[db]);
-          }
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 otr = T::tr(Ot, ln, db, ks), qtr = T::tr(Qt, ln, db, ks);
+          dv[0][db] = MFMA16(otr, pf0, dv[0][db]);
+          dv[1][db] = MFMA16(otr, pf1, dv[1][db]);
+          dk[0][db] = MFMA16(qtr, df0, dk[0][db]);
+          dk[1][db] = MFMA16(qtr, df1, dk[1][db]);
         }
+      }
     }
+    cur = cur == 2 ? 0 : cur + 1;
   }
-  if (key < s) {
-    bf16 *out = dqkv + ((int64_t)bi * s + key) * ld + (int64_t)j * 3 * D;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
 #pragma unroll
-    for (int db = 0; db < DBK; ++db)
+  for (int kg = 0; kg < 2; ++kg) {
+    if (key[kg] < s) {
+      bf16 *out = dqkv + ((int64_t)bi * s + key[kg]) * ld + (int64_t)j * 3 * D;
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
+      for (int db = 0; db < DB; ++db) {
         bf16x4 ok, ov;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          ok[i] = (bf16)(dk[db][4 * e4 + i] * scale);
-          ov[i] = (bf16)dv[db][4 * e4 + i];
+        for (int e = 0; e < 4; ++e) {
+          ok[e] = (bf16)(dk[kg][db][e] * scale);
+          ov[e] = (bf16)dv[kg][db][e];
         }
-        *reinterpret_cast<bf16x4 *>(out + D + db * 32 + 8 * e4 + 4 * g) = ok;
-        *reinterpret_cast<bf16x4 *>(out + 2 * D + db * 32 + 8 * e4 + 4 * g) = ov;
+        *reinterpret_cast<bf16x4 *>(out + D + db * 16 + 4 * g) = ok;
+        *reinterpret_cast<bf16x4 *>(out + 2 * D + db * 16 + 4 * g) = ov;
       }
+    }
   }
 }
 
 template <int D>
 int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
-  constexpr int smem = 2 * 2 * 64 * D * 2;
+  constexpr int smem = 3 * 2 * 64 * D * 2;
   static bool attr = false;
   if (!attr) {
     if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
@@ -493,7 +591,7 @@ int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float
 template <int D>
 int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a, const float *lse, const void *da,
                void *dqkv, void *ws, hipStream_t st) {
-  constexpr int smem_dq = 3 * 64 * D * 2, smem_dkv = 4 * 64 * D * 2 + 128 * 4;
+  constexpr int smem_dq = 3 * 2 * 64 * D * 2, smem_dkv = 3 * (2 * 64 * D * 2 + 512);
   static bool attr = false;
   if (!attr) {
     if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -513,6 +611,9 @@ int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a,
   return check_launch();
 }
 
+// The DMA addresses a sequence's rows with 32-bit byte offsets from its first row.
+bool fits(int s, int n, int d) { return (int64_t)s * n * 3 * d * 2 < ((int64_t)1 << 31); }
+
 }  // namespace
 
 bool attention_mfma_supported(int dtype, int d) { return dtype == MTNLG_BF16 && (d == 64 || d == 128 || d == 160); }
@@ -521,7 +622,7 @@ size_t attention_bwd_workspace_bytes(int b, int s, int n, int) { return (size_t)
 
 int attention_fwd_mfma(int b, int s, int n, int d, float scale, const void *qkv, void *a, float *lse,
                        hipStream_t stream) {
-  if (n > 65535 || b > 65535) return MTNLG_UNSUPPORTED_SHAPE;
+  if (n > 65535 || b > 65535 || !fits(s, n, d)) return MTNLG_UNSUPPORTED_SHAPE;
   switch (d) {
     case 64: return fwd_launch<64>(b, s, n, scale, qkv, a, lse, stream);
     case 128: return fwd_launch<128>(b, s, n, scale, qkv, a, lse, stream);
@@ -532,7 +633,7 @@ int attention_fwd_mfma(int b, int s, int n, int d, float scale, const void *qkv,
 
 int attention_bwd_mfma(int b, int s, int n, int d, float scale, const void *qkv, const void *a, const float *lse,
                        const void *da, void *dqkv, void *ws, hipStream_t stream) {
-  if (n > 65535 || b > 65535) return MTNLG_UNSUPPORTED_SHAPE;
+  if (n > 65535 || b > 65535 || !fits(s, n, d)) return MTNLG_UNSUPPORTED_SHAPE;
   switch (d) {
     case 64: return bwd_launch<64>(b, s, n, scale, qkv, a, lse, da, dqkv, ws, stream);
     case 128: return bwd_launch<128>(b, s, n, scale, qkv, a, lse, da, dqkv, ws, stream);

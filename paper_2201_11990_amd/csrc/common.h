@@ -61,6 +61,33 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Global -> LDS DMA (buffer_load ... lds): every lane moves 16 (or 4) bytes from base + its byte
+// offset to lds_dst + 16 (or 4) * lane; lds_dst is the same for the whole wave.  Issued as
+// inline assembly on purpose: once the compiler has seen such a write to LDS it makes the next LDS
+// read it cannot tell apart from it wait for all outstanding memory operations, which empties a
+// ring of several stages at every tile.  Kernels that use these count their outstanding DMAs
+// themselves (s_waitcnt vmcnt(N) before the barrier that publishes a stage).  The LDS address
+// travels in M0, which no other instruction of those kernels reads.
+typedef __attribute__((ext_vector_type(4))) int dma_rsrc_t;
+__device__ __forceinline__ dma_rsrc_t dma_rsrc(const void *base) {   // base: the same in every lane
+  const uint64_t a = (uint64_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return dma_rsrc_t{(int)lo, (int)(hi & 0xFFFF), -1, 0x00020000};
+}
+__device__ __forceinline__ uint32_t dma_lds_address(const void *lds_dst) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)lds_dst);
+}
+__device__ __forceinline__ void dma16(dma_rsrc_t rs, const void *lds_dst, uint32_t byte_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(dma_lds_address(lds_dst)),
+               "v"(byte_offset), "s"(rs)
+               : "memory");
+}
+__device__ __forceinline__ void dma4(dma_rsrc_t rs, const void *lds_dst, uint32_t byte_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(dma_lds_address(lds_dst)),
+               "v"(byte_offset), "s"(rs)
+               : "memory");
+}
+
 // GeLU in fp32.  tanh form: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))); erf form:
 // 0.5 z (1 + erf(z / sqrt 2)).
 __device__ __forceinline__ float gelu_f(float z, bool erf_form) {

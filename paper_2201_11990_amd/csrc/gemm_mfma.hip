@@ -480,14 +480,24 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     a_off[i] = dma_offset(wave * NI + i, g.lda, AT);
     b_off[i] = dma_offset(wave * NI + i, g.ldb, BT);
   }
+  // With a transposing LDS read in the loop the DMA goes out as inline assembly (see dma16: the
+  // compiler would put a wait for all memory operations in front of those reads); otherwise
+  // through the builtin, which the scheduling hints below can place.
   auto issue = [&](const bf16 *base, const uint32_t(&off)[NI], char *stage, int i0, int i1) {
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
     char *dst = stage + wave * (NI * 1024);
+    if constexpr (AT || BT) {
+      const dma_rsrc_t rs = dma_rsrc(base);
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      if (i >= i0 && i < i1)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16,
-                                                 (int)off[i], 0, 0, 0);
+      for (int i = 0; i < NI; ++i)
+        if (i >= i0 && i < i1) dma16(rs, dst + i * 1024, off[i]);
+    } else {
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        if (i >= i0 && i < i1)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16,
+                                                   (int)off[i], 0, 0, 0);
+    }
   };
   auto a_at = [&](int64_t k0) { return AT ? Abase + k0 * g.lda : Abase + k0; };
   auto b_at = [&](int64_t k0) { return BT ? Bbase + k0 * g.ldb : Bbase + k0; };
