@@ -61,18 +61,17 @@ struct Tile {
   static __device__ __forceinline__ int off(int row, int u) { return (row * UPR + (u ^ mask(row))) * 16; }
 
   // Wave `wave` brings rows 16 wave .. 16 wave + 15 of the tile whose first row is row0 of the
-  // matrix behind rs (row pitch ld_bytes); rows past the end repeat the last row.  A DMA
-  // instruction fills 1024 consecutive LDS bytes, lane l the 16 bytes at 16 l.
-  static __device__ __forceinline__ void dma(dma_rsrc_t rs, int row0, int rows_total, uint32_t ld_bytes,
-                                             char *stage, int wave, int lane) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int p = i * 64 + lane;
-      const int r = 16 * wave + p / UPR, u = (p % UPR) ^ mask(16 * wave + p / UPR);
-      int gr = row0 + r;
-      gr = gr < rows_total ? gr : rows_total - 1;
-      dma16(rs, stage + (wave * NI + i) * 1024, gr * ld_bytes + u * 16);
-    }
+  // matrix behind rs (row pitch ld_bytes) to LDS byte address `stage` with NI DMA instructions;
+  // rows past the end repeat the last row.  Instruction i fills 1024 consecutive LDS bytes, lane l
+  // the 16 bytes at 16 l.
+  template <int TAG>
+  static __device__ __forceinline__ void dma_one(dma_rsrc_t rs, int row0, int rows_total, uint32_t ld_bytes,
+                                                 uint32_t stage, int wave, int lane, int i) {
+    const int p = i * 64 + lane;
+    const int r = 16 * wave + p / UPR, u = (p % UPR) ^ mask(16 * wave + p / UPR);
+    int gr = row0 + r;
+    gr = gr < rows_total ? gr : rows_total - 1;
+    dma16<TAG>(rs, stage + (wave * NI + i) * 1024, gr * ld_bytes + u * 16);
   }
   // Byte offsets of a lane's fragment reads inside a tile.  mask() looks at the low four bits of a
   // row only, so a block of 16 rows further down is a constant distance away.
@@ -106,6 +105,10 @@ struct Tile {
   }
 };
 
+// call-site tags of the DMA helpers
+struct Burst { static constexpr int value = 0; };
+struct Spread { static constexpr int value = 1; };
+
 // two accumulator blocks (tile rows 32 ks + 4g + i and 32 ks + 16 + 4g + i) as the bf16 B operand
 __device__ __forceinline__ bf16x8 pack2(const f32x4 &lo, const f32x4 &hi) {
   bf16x8 o;
@@ -115,6 +118,29 @@ __device__ __forceinline__ bf16x8 pack2(const f32x4 &lo, const f32x4 &hi) {
     o[4 + i] = (bf16)hi[i];
   }
   return o;
+}
+
+// Steps 0 .. N-1 of a run of MFMAs whose A operands come from LDS: load(i) fetches the fragments
+// of step i, mma(i) multiplies with them, extra(i) is whatever else should issue during step i.
+// The loads run P steps ahead of the MFMAs, and nothing may be scheduled across a step boundary:
+// left alone, the compiler issues each LDS read right in front of its MFMA and the wave (one per
+// SIMD in these kernels) sits out the LDS latency each time.
+template <int N, int P, typename L, typename M, typename X>
+__device__ __forceinline__ void pipelined(L &&load, M &&mma, X &&extra) {
+#pragma unroll
+  for (int i = 0; i < P && i < N; ++i) load(i);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + P < N) load(i + P);
+    extra(i);
+    mma(i);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+template <int N, int P, typename L, typename M>
+__device__ __forceinline__ void pipelined(L &&load, M &&mma) {
+  pipelined<N, P>(load, mma, [](int) {});
 }
 
 // wait until at most N of this wave's memory operations are outstanding, then the workgroup barrier
@@ -155,6 +181,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
   const int q0 = qt * 128, qw = q0 + wave * 32;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
+  const uint32_t smem_addr = lds_address(smem);
 
   int qc[2];
   bf16x8 qf[2][KK];
@@ -178,10 +205,18 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
   const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
   const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
-  auto issue = [&](int t, int st) {   // tile t (clamped to the last one) into ring stage st
+  // DMA instruction i (of 2 NI) of tile t (clamped to the last one) into ring stage st.  A tile's
+  // DMAs go out one per step of the first MFMA run of the tile before: a burst of them would hold
+  // the waves at the issue port of the texture path.
+  auto issue_one = [&](auto tag, int t, int st, int i) {
+    constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    T::dma(rk, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE, wave, lane);
-    T::dma(rv, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE + T::BYTES, wave, lane);
+    if (i < T::NI) T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE, wave, lane, i);
+    else T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, wave, lane, i - T::NI);
+  };
+  auto issue = [&](int t, int st) {
+#pragma unroll
+    for (int i = 0; i < 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
@@ -192,11 +227,12 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
   int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
     wait_and_barrier<2 * T::NI>();   // tile it landed everywhere, tile it-1 no longer read
-    const int nn = cur == 0 ? 2 : cur - 1;
-    issue(it + 2, nn);
+    const int nn = cur == 0 ? 2 : cur - 1;   // stage of tile it + 2
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 <= qw + 31) {  // wave-uniform: some (query, key) pair of this wave is unmasked
+    if (kv0 > qw + 31) {  // wave-uniform: every (query, key) pair of this wave is masked
+      issue(it + 2, nn);
+    } else {
       f32x4 sc[2][4];
 #pragma unroll
       for (int qg = 0; qg < 2; ++qg)
@@ -204,14 +240,22 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
           for (int e = 0; e < 4; ++e) sc[qg][kb][e] = 0.0f;
+      {  // step i: k-step i / 2, key blocks 2 (i % 2) and 2 (i % 2) + 1
+        bf16x8 kfr[4][2];
+        pipelined<2 * KK, 3>(
+            [&](int i) {
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+              for (int h = 0; h < 2; ++h) kfr[i & 3][h] = T::nat(Kt, ln, 2 * (i & 1) + h, i >> 1);
+            },
+            [&](int i) {
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-          const bf16x8 kfr = T::nat(Kt, ln, kb, kk);
+              for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int qg = 0; qg < 2; ++qg) sc[qg][kb] = MFMA16(kfr, qf[qg][kk], sc[qg][kb]);
-        }
+                for (int qg = 0; qg < 2; ++qg)
+                  sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i & 3][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
+            },
+            [&](int i) { issue_one(Spread{}, it + 2, nn, i); });
+      }
       // element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       if (kv0 + 63 > qw) {  // wave-uniform: this tile crosses the diagonal for some row
 #pragma unroll
@@ -256,16 +300,25 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[qg][db][e] *= alpha[qg];
       }
+      {  // step i: key half i / (DB / 2), output blocks 2 (i % (DB / 2)) and + 1
+        bf16x8 pf[2][2], vfr[4][2];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 pf0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]);
-        const bf16x8 pf1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 vfr = T::tr(Vt, ln, db, ks);
-          o[0][db] = MFMA16(vfr, pf0, o[0][db]);
-          o[1][db] = MFMA16(vfr, pf1, o[1][db]);
-        }
+          for (int qg = 0; qg < 2; ++qg) pf[ks][qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
+        constexpr int HB = DB / 2;
+        pipelined<2 * HB, 3>(
+            [&](int i) {
+#pragma unroll
+              for (int h = 0; h < 2; ++h) vfr[i & 3][h] = T::tr(Vt, ln, 2 * (i % HB) + h, i / HB);
+            },
+            [&](int i) {
+#pragma unroll
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int qg = 0; qg < 2; ++qg)
+                  o[qg][2 * (i % HB) + h] = MFMA16(vfr[i & 3][h], pf[i / HB][qg], o[qg][2 * (i % HB) + h]);
+            });
       }
     }
     cur = cur == 2 ? 0 : cur + 1;
@@ -307,6 +360,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   const int q0 = qt * 128, qw = q0 + wave * 32;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
+  const uint32_t smem_addr = lds_address(smem);
 
   int qc[2];
   bf16x8 qf[2][KK], dof[2][KK];
@@ -342,10 +396,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
   const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
-  auto issue = [&](int t, int st) {
+  // as in the forward kernel: one DMA instruction per step of the first MFMA run
+  auto issue_one = [&](auto tag, int t, int st, int i) {
+    constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    T::dma(rk, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE, wave, lane);
-    T::dma(rv, tt * 64, s, (uint32_t)(ld * 2), smem + st * STAGE + T::BYTES, wave, lane);
+    if (i < T::NI) T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE, wave, lane, i);
+    else T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, wave, lane, i - T::NI);
+  };
+  auto issue = [&](int t, int st) {
+#pragma unroll
+    for (int i = 0; i < 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
@@ -363,10 +423,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   for (int it = 0; it < ntiles; ++it) {
     wait_and_barrier<2 * T::NI>();
     const int nn = cur == 0 ? 2 : cur - 1;
-    issue(it + 2, nn);
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 <= qw + 31) {
+    if (kv0 > qw + 31) {
+      issue(it + 2, nn);
+    } else {
       f32x4 sc[2][4], pc[2][4];
 #pragma unroll
       for (int qg = 0; qg < 2; ++qg)
@@ -374,17 +435,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
           for (int e = 0; e < 4; ++e) sc[qg][kb][e] = pc[qg][kb][e] = 0.0f;
+      {  // step i: k-step i / 2, key blocks 2 (i % 2) and + 1
+        bf16x8 kfr[3][2], vfr[3][2];
+        pipelined<2 * KK, 2>(
+            [&](int i) {
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+              for (int h = 0; h < 2; ++h) {
+                kfr[i % 3][h] = T::nat(Kt, ln, 2 * (i & 1) + h, i >> 1);
+                vfr[i % 3][h] = T::nat(Vt, ln, 2 * (i & 1) + h, i >> 1);
+              }
+            },
+            [&](int i) {
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-          const bf16x8 kfr = T::nat(Kt, ln, kb, kk), vfr = T::nat(Vt, ln, kb, kk);
+              for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int qg = 0; qg < 2; ++qg) {
-            sc[qg][kb] = MFMA16(kfr, qf[qg][kk], sc[qg][kb]);
-            pc[qg][kb] = MFMA16(vfr, dof[qg][kk], pc[qg][kb]);
-          }
-        }
+                for (int qg = 0; qg < 2; ++qg) {
+                  sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i % 3][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
+                  pc[qg][2 * (i & 1) + h] = MFMA16(vfr[i % 3][h], dof[qg][i >> 1], pc[qg][2 * (i & 1) + h]);
+                }
+            },
+            [&](int i) { issue_one(Spread{}, it + 2, nn, i); });
+      }
       // dS^T = P^T o (dP^T - D); element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       const bool diag = kv0 + 63 > qw;  // wave-uniform: diagonal (or past-the-end keys) in this tile
 #pragma unroll
@@ -397,16 +468,25 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
             if (diag && kv0 + 16 * kb + 4 * g + e > qc[qg]) p = 0.0f;
             sc[qg][kb][e] = p * (pc[qg][kb][e] - dsum[qg]);
           }
+      {  // step i: key half i / (DB / 2), output blocks 2 (i % (DB / 2)) and + 1
+        bf16x8 df[2][2], ktr[4][2];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 df0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]);
-        const bf16x8 df1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 ktr = T::tr(Kt, ln, db, ks);
-          dq[0][db] = MFMA16(ktr, df0, dq[0][db]);
-          dq[1][db] = MFMA16(ktr, df1, dq[1][db]);
-        }
+          for (int qg = 0; qg < 2; ++qg) df[ks][qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
+        constexpr int HB = DB / 2;
+        pipelined<2 * HB, 3>(
+            [&](int i) {
+#pragma unroll
+              for (int h = 0; h < 2; ++h) ktr[i & 3][h] = T::tr(Kt, ln, 2 * (i % HB) + h, i / HB);
+            },
+            [&](int i) {
+#pragma unroll
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int qg = 0; qg < 2; ++qg)
+                  dq[qg][2 * (i % HB) + h] = MFMA16(ktr[i & 3][h], df[i / HB][qg], dq[qg][2 * (i % HB) + h]);
+            });
       }
     }
     cur = cur == 2 ? 0 : cur + 1;
@@ -446,6 +526,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   const int k0 = kt * 128, kw = k0 + wave * 32;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
+  const uint32_t smem_addr = lds_address(smem);
 
   int key[2];
   bf16x8 kf[2][KK], vf[2][KK];
@@ -473,15 +554,25 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   // the same number of memory operations, which the counted waits below rely on)
   const dma_rsrc_t rstat =
       dma_rsrc(((wave & 1) ? Dvec : lse) + ((int64_t)bi * n + j) * s);
-  auto issue = [&](int t, int st) {
+  // DMA instruction i (of 2 NI + 1) of tile t into ring stage st, one per step as in the forward kernel
+  auto issue_one = [&](auto tag, int t, int st, int i) {
+    constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
     const int row0 = (t_first + tt) * 64;
-    char *stage = smem + st * STAGE;
-    T::dma(rq, row0, s, (uint32_t)(ld * 2), stage, wave, lane);
-    T::dma(ro, row0, s, (uint32_t)(pld * 2), stage + T::BYTES, wave, lane);
-    int qq = row0 + lane;
-    qq = qq < s ? qq : s - 1;
-    dma4(rstat, stage + 2 * T::BYTES + (wave & 1) * 256, qq * 4);
+    const uint32_t stage = smem_addr + st * STAGE;
+    if (i < T::NI) {
+      T::template dma_one<TAG>(rq, row0, s, (uint32_t)(ld * 2), stage, wave, lane, i);
+    } else if (i < 2 * T::NI) {
+      T::template dma_one<TAG>(ro, row0, s, (uint32_t)(pld * 2), stage + T::BYTES, wave, lane, i - T::NI);
+    } else {
+      int qq = row0 + lane;
+      qq = qq < s ? qq : s - 1;
+      dma4<TAG>(rstat, stage + 2 * T::BYTES + (wave & 1) * 256, qq * 4);
+    }
+  };
+  auto issue = [&](int t, int st) {
+#pragma unroll
+    for (int i = 0; i <= 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
@@ -496,11 +587,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   for (int it = 0; it < ntiles; ++it) {
     wait_and_barrier<2 * T::NI + 1>();
     const int nn = cur == 0 ? 2 : cur - 1;
-    issue(it + 2, nn);
     const char *Qt = smem + cur * STAGE, *Ot = Qt + T::BYTES;
     const float *stat = reinterpret_cast<const float *>(Qt + 2 * T::BYTES);
     const int q0 = (t_first + it) * 64;
-    if (q0 + 63 >= kw) {  // wave-uniform: some query of the tile sees a key of this wave
+    if (q0 + 63 < kw) {  // wave-uniform: no query of the tile sees a key of this wave
+      issue(it + 2, nn);
+    } else {
       f32x4 sc[2][4], pc[2][4];
 #pragma unroll
       for (int kg = 0; kg < 2; ++kg)
@@ -508,17 +600,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
         for (int qb = 0; qb < 4; ++qb)
 #pragma unroll
           for (int e = 0; e < 4; ++e) sc[kg][qb][e] = pc[kg][qb][e] = 0.0f;
+      {  // step i: k-step i / 2, query blocks 2 (i % 2) and + 1
+        bf16x8 qfr[3][2], ofr[3][2];
+        pipelined<2 * KK, 2>(
+            [&](int i) {
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+              for (int h = 0; h < 2; ++h) {
+                qfr[i % 3][h] = T::nat(Qt, ln, 2 * (i & 1) + h, i >> 1);
+                ofr[i % 3][h] = T::nat(Ot, ln, 2 * (i & 1) + h, i >> 1);
+              }
+            },
+            [&](int i) {
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
-          const bf16x8 qfr = T::nat(Qt, ln, qb, kk), ofr = T::nat(Ot, ln, qb, kk);
+              for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int kg = 0; kg < 2; ++kg) {
-            sc[kg][qb] = MFMA16(qfr, kf[kg][kk], sc[kg][qb]);
-            pc[kg][qb] = MFMA16(ofr, vf[kg][kk], pc[kg][qb]);
-          }
-        }
+                for (int kg = 0; kg < 2; ++kg) {
+                  sc[kg][2 * (i & 1) + h] = MFMA16(qfr[i % 3][h], kf[kg][i >> 1], sc[kg][2 * (i & 1) + h]);
+                  pc[kg][2 * (i & 1) + h] = MFMA16(ofr[i % 3][h], vf[kg][i >> 1], pc[kg][2 * (i & 1) + h]);
+                }
+            },
+            [&](int i) {
+              issue_one(Spread{}, it + 2, nn, i);
+              if (i == 2 * KK - 1) issue_one(Spread{}, it + 2, nn, 2 * T::NI);
+            });
+      }
       // element (kg, qb, e): query q0 + 16 qb + 4 g + e, key key[kg]
       const bool edge = q0 < kw + 32 || q0 + 63 >= s;  // wave-uniform: diagonal or past-the-end queries
 #pragma unroll
@@ -536,18 +641,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
             pc[kg][qb][e] = p * (pc[kg][qb][e] - dd[e]);
           }
       }
+      {  // step i: query half i / DB, output block i % DB
+        bf16x8 pf[2][2], df[2][2], otr[4], qtr[4];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 pf0 = pack2(sc[0][2 * ks], sc[0][2 * ks + 1]), pf1 = pack2(sc[1][2 * ks], sc[1][2 * ks + 1]);
-        const bf16x8 df0 = pack2(pc[0][2 * ks], pc[0][2 * ks + 1]), df1 = pack2(pc[1][2 * ks], pc[1][2 * ks + 1]);
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 otr = T::tr(Ot, ln, db, ks), qtr = T::tr(Qt, ln, db, ks);
-          dv[0][db] = MFMA16(otr, pf0, dv[0][db]);
-          dv[1][db] = MFMA16(otr, pf1, dv[1][db]);
-          dk[0][db] = MFMA16(qtr, df0, dk[0][db]);
-          dk[1][db] = MFMA16(qtr, df1, dk[1][db]);
-        }
+          for (int kg = 0; kg < 2; ++kg) {
+            pf[ks][kg] = pack2(sc[kg][2 * ks], sc[kg][2 * ks + 1]);
+            df[ks][kg] = pack2(pc[kg][2 * ks], pc[kg][2 * ks + 1]);
+          }
+        pipelined<2 * DB, 3>(
+            [&](int i) {
+              otr[i & 3] = T::tr(Ot, ln, i % DB, i / DB);
+              qtr[i & 3] = T::tr(Qt, ln, i % DB, i / DB);
+            },
+            [&](int i) {
+#pragma unroll
+              for (int kg = 0; kg < 2; ++kg) {
+                dv[kg][i % DB] = MFMA16(otr[i & 3], pf[i / DB][kg], dv[kg][i % DB]);
+                dk[kg][i % DB] = MFMA16(qtr[i & 3], df[i / DB][kg], dk[kg][i % DB]);
+              }
+            });
       }
     }
     cur = cur == 2 ? 0 : cur + 1;

@@ -62,7 +62,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // Global -> LDS DMA (buffer_load ... lds): every lane moves 16 (or 4) bytes from base + its byte
-// offset to lds_dst + 16 (or 4) * lane; lds_dst is the same for the whole wave.  Issued as
+// offset to LDS byte address lds_dst + 16 (or 4) * lane; lds_dst is the same for the whole wave.  Issued as
 // inline assembly on purpose: once the compiler has seen such a write to LDS it makes the next LDS
 // read it cannot tell apart from it wait for all outstanding memory operations, which empties a
 // ring of several stages at every tile.  Kernels that use these count their outstanding DMAs
@@ -74,17 +74,24 @@ __device__ __forceinline__ dma_rsrc_t dma_rsrc(const void *base) {   // base: th
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
   return dma_rsrc_t{(int)lo, (int)(hi & 0xFFFF), -1, 0x00020000};
 }
-__device__ __forceinline__ uint32_t dma_lds_address(const void *lds_dst) {
-  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)lds_dst);
+// LDS byte address of a pointer into shared memory (what M0 takes)
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
-__device__ __forceinline__ void dma16(dma_rsrc_t rs, const void *lds_dst, uint32_t byte_offset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(dma_lds_address(lds_dst)),
-               "v"(byte_offset), "s"(rs)
+// TAG only tells call sites apart: the compiler merges identical asm statements on the two sides
+// of a branch into one burst in front of it, which is exactly what spreading them tries to avoid.
+template <int TAG = 0>
+__device__ __forceinline__ void dma16(dma_rsrc_t rs, uint32_t lds_dst, uint32_t byte_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds ; site %3" ::"s"(
+                   __builtin_amdgcn_readfirstlane(lds_dst)),
+               "v"(byte_offset), "s"(rs), "n"(TAG)
                : "memory");
 }
-__device__ __forceinline__ void dma4(dma_rsrc_t rs, const void *lds_dst, uint32_t byte_offset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(dma_lds_address(lds_dst)),
-               "v"(byte_offset), "s"(rs)
+template <int TAG = 0>
+__device__ __forceinline__ void dma4(dma_rsrc_t rs, uint32_t lds_dst, uint32_t byte_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds ; site %3" ::"s"(
+                   __builtin_amdgcn_readfirstlane(lds_dst)),
+               "v"(byte_offset), "s"(rs), "n"(TAG)
                : "memory");
 }
 

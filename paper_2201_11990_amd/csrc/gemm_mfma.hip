@@ -487,9 +487,10 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     char *dst = stage + wave * (NI * 1024);
     if constexpr (AT || BT) {
       const dma_rsrc_t rs = dma_rsrc(base);
+      const uint32_t dst_addr = lds_address(dst);
 #pragma unroll
       for (int i = 0; i < NI; ++i)
-        if (i >= i0 && i < i1) dma16(rs, dst + i * 1024, off[i]);
+        if (i >= i0 && i < i1) dma16(rs, dst_addr + i * 1024, off[i]);
     } else {
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
 #pragma unroll
