@@ -125,11 +125,14 @@ __device__ __forceinline__ bf16x8 pack2(const f32x4 &lo, const f32x4 &hi) {
 // The loads run P steps ahead of the MFMAs, and nothing may be scheduled across a step boundary:
 // left alone, the compiler issues each LDS read right in front of its MFMA and the wave (one per
 // SIMD in these kernels) sits out the LDS latency each time.
-template <int N, int P, typename L, typename M, typename X>
-__device__ __forceinline__ void pipelined(L &&load, M &&mma, X &&extra) {
+template <int N, int P, typename L>
+__device__ __forceinline__ void pipelined_start(L &&load) {
 #pragma unroll
   for (int i = 0; i < P && i < N; ++i) load(i);
   __builtin_amdgcn_sched_barrier(0);
+}
+template <int N, int P, typename L, typename M, typename X>
+__device__ __forceinline__ void pipelined_run(L &&load, M &&mma, X &&extra) {
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     if (i + P < N) load(i + P);
@@ -137,6 +140,11 @@ __device__ __forceinline__ void pipelined(L &&load, M &&mma, X &&extra) {
     mma(i);
     __builtin_amdgcn_sched_barrier(0);
   }
+}
+template <int N, int P, typename L, typename M, typename X>
+__device__ __forceinline__ void pipelined(L &&load, M &&mma, X &&extra) {
+  pipelined_start<N, P>(load);
+  pipelined_run<N, P>(load, mma, extra);
 }
 template <int N, int P, typename L, typename M>
 __device__ __forceinline__ void pipelined(L &&load, M &&mma) {
@@ -155,6 +163,12 @@ __device__ __forceinline__ void wait_and_barrier() {
 template <typename V>
 __device__ __forceinline__ void arrive(V &v) {
   asm volatile("" : "+v"(v));
+}
+// An accumulator block that only MFMAs touch inside the main loop stays in the accumulation
+// registers: without this hint at the top of the loop body the compiler moves every block to the
+// ordinary registers and back once per tile.
+__device__ __forceinline__ void keep_acc(f32x4 &v) {
+  asm volatile("" : "+a"(v));
 }
 
 // sum / maximum over the four lanes that share lane % 16
@@ -277,7 +291,10 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 #pragma unroll
           for (int e = 0; e < 4; ++e) mx = fmaxf(mx, sc[qg][kb][e]);
         mx = quad_max(mx);
-        const float m_new = fmaxf(m[qg], mx);  // finite from the first tile on (key 0 is never masked)
+        // The reference maximum only follows when the row maximum has outgrown it by more than
+        // 2^8 in the exponent's units (any reference gives the same sums; this one keeps p <= 256
+        // and makes rescaling O rare).  Finite from the first tile on: key 0 is never masked.
+        const float m_new = mx * c > m[qg] * c + 8.0f ? mx : m[qg];
         const float mc = m_new * c;
         float rs = 0.0f;
 #pragma unroll
@@ -422,6 +439,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
     wait_and_barrier<2 * T::NI>();
+#pragma unroll
+    for (int qg = 0; qg < 2; ++qg)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) keep_acc(dq[qg][db]);
     const int nn = cur == 0 ? 2 : cur - 1;
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
@@ -436,13 +457,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
 #pragma unroll
           for (int e = 0; e < 4; ++e) sc[qg][kb][e] = pc[qg][kb][e] = 0.0f;
       {  // step i: k-step i / 2, key blocks 2 (i % 2) and + 1
-        bf16x8 kfr[3][2], vfr[3][2];
-        pipelined<2 * KK, 2>(
+        bf16x8 kfr[2][2], vfr[2][2];
+        pipelined<2 * KK, 1>(
             [&](int i) {
 #pragma unroll
               for (int h = 0; h < 2; ++h) {
-                kfr[i % 3][h] = T::nat(Kt, ln, 2 * (i & 1) + h, i >> 1);
-                vfr[i % 3][h] = T::nat(Vt, ln, 2 * (i & 1) + h, i >> 1);
+                kfr[i & 1][h] = T::nat(Kt, ln, 2 * (i & 1) + h, i >> 1);
+                vfr[i & 1][h] = T::nat(Vt, ln, 2 * (i & 1) + h, i >> 1);
               }
             },
             [&](int i) {
@@ -450,43 +471,46 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
               for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int qg = 0; qg < 2; ++qg) {
-                  sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i % 3][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
-                  pc[qg][2 * (i & 1) + h] = MFMA16(vfr[i % 3][h], dof[qg][i >> 1], pc[qg][2 * (i & 1) + h]);
+                  sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i & 1][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
+                  pc[qg][2 * (i & 1) + h] = MFMA16(vfr[i & 1][h], dof[qg][i >> 1], pc[qg][2 * (i & 1) + h]);
                 }
             },
             [&](int i) { issue_one(Spread{}, it + 2, nn, i); });
       }
       // dS^T = P^T o (dP^T - D); element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       const bool diag = kv0 + 63 > qw;  // wave-uniform: diagonal (or past-the-end keys) in this tile
+      // one half of the tile's keys at a time: dS of key blocks 2 ks, 2 ks + 1, then their 2 DB
+      // MFMAs, step i = output blocks 2 i, 2 i + 1
 #pragma unroll
-      for (int qg = 0; qg < 2; ++qg)
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 df[2], ktr[4][2];
+        auto load = [&](int i) {
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
+          for (int h = 0; h < 2; ++h) ktr[i & 3][h] = T::tr(Kt, ln, 2 * i + h, ks);
+        };
+        pipelined_start<DB / 2, 3>(load);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float p = fast_exp2(fmaf(sc[qg][kb][e], c, -lse2[qg]));
-            if (diag && kv0 + 16 * kb + 4 * g + e > qc[qg]) p = 0.0f;
-            sc[qg][kb][e] = p * (pc[qg][kb][e] - dsum[qg]);
-          }
-      {  // step i: key half i / (DB / 2), output blocks 2 (i % (DB / 2)) and + 1
-        bf16x8 df[2][2], ktr[4][2];
+        for (int qg = 0; qg < 2; ++qg)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+          for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int qg = 0; qg < 2; ++qg) df[ks][qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
-        constexpr int HB = DB / 2;
-        pipelined<2 * HB, 3>(
-            [&](int i) {
+            for (int e = 0; e < 4; ++e) {
+              const int kb = 2 * ks + h;
+              float p = fast_exp2(fmaf(sc[qg][kb][e], c, -lse2[qg]));
+              if (diag && kv0 + 16 * kb + 4 * g + e > qc[qg]) p = 0.0f;
+              sc[qg][kb][e] = p * (pc[qg][kb][e] - dsum[qg]);
+            }
 #pragma unroll
-              for (int h = 0; h < 2; ++h) ktr[i & 3][h] = T::tr(Kt, ln, 2 * (i % HB) + h, i / HB);
-            },
+        for (int qg = 0; qg < 2; ++qg) df[qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
+        pipelined_run<DB / 2, 3>(
+            load,
             [&](int i) {
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int qg = 0; qg < 2; ++qg)
-                  dq[qg][2 * (i % HB) + h] = MFMA16(ktr[i & 3][h], df[i / HB][qg], dq[qg][2 * (i % HB) + h]);
-            });
+                for (int qg = 0; qg < 2; ++qg) dq[qg][2 * i + h] = MFMA16(ktr[i & 3][h], df[qg], dq[qg][2 * i + h]);
+            },
+            [](int) {});
       }
     }
     cur = cur == 2 ? 0 : cur + 1;
