@@ -5,9 +5,9 @@
 //   backward with D_t = da_t . a_t :  dP = da v^T,  dS = P o (dP - D),
 //   dq = scale dS k,  dk = scale dS^T q,  dv = P^T da.
 //
-// Three kernels, one geometry.  A workgroup of four waves owns 128 rows of one side
-// (queries for forward and dq, keys for dk/dv), 32 per wave, held in registers as MFMA
-// B operands (two groups of 16, one row per lane column); the other side streams through
+// Three kernels, one geometry.  A workgroup owns 128 rows of one side (queries for forward
+// and dq, keys for dk/dv), 16 or 32 per wave (eight or four waves), held in registers as MFMA
+// B operands (groups of 16, one row per lane column); the other side streams through
 // LDS in tiles of 64 rows, brought in by LDS DMA (buffer_load ... lds, no staging
 // registers) three tiles deep, one workgroup barrier per tile.
 //
@@ -182,8 +182,8 @@ __device__ __forceinline__ float quad_max(float v) {
 }
 
 // ------------------------------------------------------------------ forward
-template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
+template <int D, int G>
+__global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
                                                        bf16 *__restrict__ a, float *__restrict__ lse) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
@@ -192,64 +192,75 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const int q0 = qt * 128, qw = q0 + wave * 32;
+  const int q0 = qt * 128, qw = q0 + wave * (16 * G);
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
 
-  int qc[2];
-  bf16x8 qf[2][KK];
+  int qc[G];
+  bf16x8 qf[G][KK];
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg) {
+  for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
     qc[qg] = q < s ? q : s - 1;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
       qf[qg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)qc[qg] * ld + 32 * kk + 8 * g);
   }
-  f32x4 o[2][DB];
+  f32x4 o[G][DB];
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg)
+  for (int qg = 0; qg < G; ++qg)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e = 0; e < 4; ++e) o[qg][db][e] = 0.0f;
-  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};   // l: this lane's share of the row sum
+  float m[G], l[G];   // l: this lane's share of the row sum
+#pragma unroll
+  for (int qg = 0; qg < G; ++qg) {
+    m[qg] = -INFINITY;
+    l[qg] = 0.0f;
+  }
 
   const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
-  const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
-  // DMA instruction i (of 2 NI) of tile t (clamped to the last one) into ring stage st.  A tile's
+  // Who brings what: with four waves (G = 2) wave w brings rows 16 w .. 16 w + 15 of the K tile and of
+  // the V tile; with eight (G = 1) waves 0-3 bring the K tile, waves 4-7 the V tile.
+  constexpr int IPW = G * T::NI;   // DMA instructions per wave and tile
+  const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
+  const dma_rsrc_t rk = dma_rsrc(base + D + half * D), rv = dma_rsrc(base + 2 * D);
+  // DMA instruction i (of IPW) of tile t (clamped to the last one) into ring stage st.  A tile's
   // DMAs go out one per step of the first MFMA run of the tile before: a burst of them would hold
   // the waves at the issue port of the texture path.
   auto issue_one = [&](auto tag, int t, int st, int i) {
     constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    if (i < T::NI) T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE, wave, lane, i);
-    else T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, wave, lane, i - T::NI);
+    if (G == 1 || i < T::NI)
+      T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + half * T::BYTES, quarter, lane, i);
+    else
+      T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, quarter, lane, i - T::NI);
   };
   auto issue = [&](int t, int st) {
 #pragma unroll
-    for (int i = 0; i < 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
+    for (int i = 0; i < IPW; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg)
+  for (int qg = 0; qg < G; ++qg)
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) arrive(qf[qg][kk]);
   int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
-    wait_and_barrier<2 * T::NI>();   // tile it landed everywhere, tile it-1 no longer read
+    wait_and_barrier<IPW>();   // tile it landed everywhere, tile it-1 no longer read
     const int nn = cur == 0 ? 2 : cur - 1;   // stage of tile it + 2
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 > qw + 31) {  // wave-uniform: every (query, key) pair of this wave is masked
+    if (kv0 > qw + (16 * G - 1)) {  // wave-uniform: every (query, key) pair of this wave is masked
       issue(it + 2, nn);
     } else {
-      f32x4 sc[2][4];
+      f32x4 sc[G][4];
 #pragma unroll
-      for (int qg = 0; qg < 2; ++qg)
+      for (int qg = 0; qg < G; ++qg)
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -265,15 +276,17 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int qg = 0; qg < 2; ++qg)
+                for (int qg = 0; qg < G; ++qg)
                   sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i & 3][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
             },
-            [&](int i) { issue_one(Spread{}, it + 2, nn, i); });
+            [&](int i) {
+              if (i < IPW) issue_one(Spread{}, it + 2, nn, i);
+            });
       }
       // element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       if (kv0 + 63 > qw) {  // wave-uniform: this tile crosses the diagonal for some row
 #pragma unroll
-        for (int qg = 0; qg < 2; ++qg)
+        for (int qg = 0; qg < G; ++qg)
 #pragma unroll
           for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -282,9 +295,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
       }
       // m tracks the running maximum of the raw scores; exponents are taken in base 2 with the
       // scale folded in: p = 2^(s c - m c).
-      float alpha[2];
+      float alpha[G];
 #pragma unroll
-      for (int qg = 0; qg < 2; ++qg) {
+      for (int qg = 0; qg < G; ++qg) {
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
@@ -309,20 +322,23 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
         l[qg] = l[qg] * alpha[qg] + rs;
         m[qg] = m_new;
       }
-      if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {  // a maximum moved: rescale O
+      bool moved = false;
 #pragma unroll
-        for (int qg = 0; qg < 2; ++qg)
+      for (int qg = 0; qg < G; ++qg) moved = moved || alpha[qg] != 1.0f;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {  // a reference maximum moved: rescale O
+#pragma unroll
+        for (int qg = 0; qg < G; ++qg)
 #pragma unroll
           for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[qg][db][e] *= alpha[qg];
       }
       {  // step i: key half i / (DB / 2), output blocks 2 (i % (DB / 2)) and + 1
-        bf16x8 pf[2][2], vfr[4][2];
+        bf16x8 pf[2][G], vfr[4][2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int qg = 0; qg < 2; ++qg) pf[ks][qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
+          for (int qg = 0; qg < G; ++qg) pf[ks][qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
         constexpr int HB = DB / 2;
         pipelined<2 * HB, 3>(
             [&](int i) {
@@ -333,7 +349,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int qg = 0; qg < 2; ++qg)
+                for (int qg = 0; qg < G; ++qg)
                   o[qg][2 * (i % HB) + h] = MFMA16(vfr[i & 3][h], pf[i / HB][qg], o[qg][2 * (i % HB) + h]);
             });
       }
@@ -343,7 +359,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped look-ahead tiles
 
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg) {
+  for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
     const float lsum = quad_sum(l[qg]);
     if (q < s) {
@@ -362,8 +378,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int n, float scale
 }
 
 // ------------------------------------------------------------------ backward: dq (and D)
-template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
+template <int D, int G>
+__global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
                                                           const bf16 *__restrict__ a, const float *__restrict__ lse,
                                                           const bf16 *__restrict__ da, bf16 *__restrict__ dqkv,
                                                           float *__restrict__ Dvec) {
@@ -374,16 +390,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const int q0 = qt * 128, qw = q0 + wave * 32;
+  const int q0 = qt * 128, qw = q0 + wave * (16 * G);
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
 
-  int qc[2];
-  bf16x8 qf[2][KK], dof[2][KK];
-  float dsum[2], lse2[2];
+  int qc[G];
+  bf16x8 qf[G][KK], dof[G][KK];
+  float dsum[G], lse2[G];
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg) {
+  for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
     qc[qg] = q < s ? q : s - 1;
     const bf16 *dar = da + ((int64_t)bi * s + qc[qg]) * pld + (int64_t)j * D;
@@ -402,9 +418,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
     if (q < s && g == 0) Dvec[((int64_t)bi * n + j) * s + q] = dsum[qg];
   }
 
-  f32x4 dq[2][DB];
+  f32x4 dq[G][DB];
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg)
+  for (int qg = 0; qg < G; ++qg)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -412,22 +428,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
 
   const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
   const int ntiles = last / 64 + 1;
-  const dma_rsrc_t rk = dma_rsrc(base + D), rv = dma_rsrc(base + 2 * D);
-  // as in the forward kernel: one DMA instruction per step of the first MFMA run
+  // tile DMAs as in the forward kernel
+  constexpr int IPW = G * T::NI;
+  const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
+  const dma_rsrc_t rk = dma_rsrc(base + D + half * D), rv = dma_rsrc(base + 2 * D);
   auto issue_one = [&](auto tag, int t, int st, int i) {
     constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    if (i < T::NI) T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE, wave, lane, i);
-    else T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, wave, lane, i - T::NI);
+    if (G == 1 || i < T::NI)
+      T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + half * T::BYTES, quarter, lane, i);
+    else
+      T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, quarter, lane, i - T::NI);
   };
   auto issue = [&](int t, int st) {
 #pragma unroll
-    for (int i = 0; i < 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
+    for (int i = 0; i < IPW; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg) {
+  for (int qg = 0; qg < G; ++qg) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       arrive(qf[qg][kk]);
@@ -438,20 +458,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   }
   int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
-    wait_and_barrier<2 * T::NI>();
+    wait_and_barrier<IPW>();
 #pragma unroll
-    for (int qg = 0; qg < 2; ++qg)
+    for (int qg = 0; qg < G; ++qg)
 #pragma unroll
       for (int db = 0; db < DB; ++db) keep_acc(dq[qg][db]);
     const int nn = cur == 0 ? 2 : cur - 1;
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 > qw + 31) {
+    if (kv0 > qw + (16 * G - 1)) {
       issue(it + 2, nn);
     } else {
-      f32x4 sc[2][4], pc[2][4];
+      f32x4 sc[G][4], pc[G][4];
 #pragma unroll
-      for (int qg = 0; qg < 2; ++qg)
+      for (int qg = 0; qg < G; ++qg)
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -470,12 +490,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int qg = 0; qg < 2; ++qg) {
+                for (int qg = 0; qg < G; ++qg) {
                   sc[qg][2 * (i & 1) + h] = MFMA16(kfr[i & 1][h], qf[qg][i >> 1], sc[qg][2 * (i & 1) + h]);
                   pc[qg][2 * (i & 1) + h] = MFMA16(vfr[i & 1][h], dof[qg][i >> 1], pc[qg][2 * (i & 1) + h]);
                 }
             },
-            [&](int i) { issue_one(Spread{}, it + 2, nn, i); });
+            [&](int i) {
+              if (i < IPW) issue_one(Spread{}, it + 2, nn, i);
+            });
       }
       // dS^T = P^T o (dP^T - D); element (qg, kb, e): key kv0 + 16 kb + 4 g + e, query qc[qg]
       const bool diag = kv0 + 63 > qw;  // wave-uniform: diagonal (or past-the-end keys) in this tile
@@ -483,14 +505,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
       // MFMAs, step i = output blocks 2 i, 2 i + 1
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        bf16x8 df[2], ktr[4][2];
+        bf16x8 df[G], ktr[4][2];
         auto load = [&](int i) {
 #pragma unroll
           for (int h = 0; h < 2; ++h) ktr[i & 3][h] = T::tr(Kt, ln, 2 * i + h, ks);
         };
         pipelined_start<DB / 2, 3>(load);
 #pragma unroll
-        for (int qg = 0; qg < 2; ++qg)
+        for (int qg = 0; qg < G; ++qg)
 #pragma unroll
           for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -501,14 +523,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
               sc[qg][kb][e] = p * (pc[qg][kb][e] - dsum[qg]);
             }
 #pragma unroll
-        for (int qg = 0; qg < 2; ++qg) df[qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
+        for (int qg = 0; qg < G; ++qg) df[qg] = pack2(sc[qg][2 * ks], sc[qg][2 * ks + 1]);
         pipelined_run<DB / 2, 3>(
             load,
             [&](int i) {
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int qg = 0; qg < 2; ++qg) dq[qg][2 * i + h] = MFMA16(ktr[i & 3][h], df[qg], dq[qg][2 * i + h]);
+                for (int qg = 0; qg < G; ++qg) dq[qg][2 * i + h] = MFMA16(ktr[i & 3][h], df[qg], dq[qg][2 * i + h]);
             },
             [](int) {});
       }
@@ -518,7 +540,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
-  for (int qg = 0; qg < 2; ++qg) {
+  for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
     if (q < s) {
       bf16 *out = dqkv + ((int64_t)bi * s + q) * ld + (int64_t)j * 3 * D;
@@ -534,8 +556,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int s, int n, float sc
 }
 
 // ------------------------------------------------------------------ backward: dk, dv
-template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
+template <int D, int G>
+__global__ __launch_bounds__(512 / G) void attn_bwd_dkv_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
                                                            const float *__restrict__ lse,
                                                            const float *__restrict__ Dvec,
                                                            const bf16 *__restrict__ da, bf16 *__restrict__ dqkv) {
@@ -547,15 +569,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
   const bf16 *dab = da + (int64_t)bi * s * pld + (int64_t)j * D;
-  const int k0 = kt * 128, kw = k0 + wave * 32;
+  const int k0 = kt * 128, kw = k0 + wave * (16 * G);
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
 
-  int key[2];
-  bf16x8 kf[2][KK], vf[2][KK];
+  int key[G];
+  bf16x8 kf[G][KK], vf[G][KK];
 #pragma unroll
-  for (int kg = 0; kg < 2; ++kg) {
+  for (int kg = 0; kg < G; ++kg) {
     key[kg] = kw + 16 * kg + lr;
     const int keyc = key[kg] < s ? key[kg] : s - 1;
 #pragma unroll
@@ -564,44 +586,46 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
       vf[kg][kk] = *reinterpret_cast<const bf16x8 *>(base + (int64_t)keyc * ld + 2 * D + 32 * kk + 8 * g);
     }
   }
-  f32x4 dk[2][DB], dv[2][DB];
+  f32x4 dk[G][DB], dv[G][DB];
 #pragma unroll
-  for (int kg = 0; kg < 2; ++kg)
+  for (int kg = 0; kg < G; ++kg)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e = 0; e < 4; ++e) dk[kg][db][e] = dv[kg][db][e] = 0.0f;
 
   const int t_first = k0 / 64, ntiles = (s + 63) / 64 - t_first;
-  const dma_rsrc_t rq = dma_rsrc(base), ro = dma_rsrc(dab);
-  // even waves bring the tile's lse values, odd waves its D values (twice each: every wave issues
-  // the same number of memory operations, which the counted waits below rely on)
-  const dma_rsrc_t rstat =
-      dma_rsrc(((wave & 1) ? Dvec : lse) + ((int64_t)bi * n + j) * s);
-  // DMA instruction i (of 2 NI + 1) of tile t into ring stage st, one per step as in the forward kernel
-  auto issue_one = [&](auto tag, int t, int st, int i) {
+  // tile DMAs as in the forward kernel (Q tile and dO tile), plus one instruction per wave for the
+  // tile's lse values (even waves) or D values (odd waves); those arrive two or four times over, so
+  // that every wave issues the same number of memory operations, which the counted waits rely on
+  constexpr int IPW = G * T::NI;
+  const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
+  const dma_rsrc_t rq = dma_rsrc(half ? dab : base), ro = dma_rsrc(dab);
+  const uint32_t pitch_q = (uint32_t)((half ? pld : ld) * 2);
+  const dma_rsrc_t rstat = dma_rsrc(((wave & 1) ? Dvec : lse) + ((int64_t)bi * n + j) * s);
+  auto issue_one = [&](auto tag, int t, int st, int i) {   // i == IPW: the statistics
     constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
     const int row0 = (t_first + tt) * 64;
     const uint32_t stage = smem_addr + st * STAGE;
-    if (i < T::NI) {
-      T::template dma_one<TAG>(rq, row0, s, (uint32_t)(ld * 2), stage, wave, lane, i);
-    } else if (i < 2 * T::NI) {
-      T::template dma_one<TAG>(ro, row0, s, (uint32_t)(pld * 2), stage + T::BYTES, wave, lane, i - T::NI);
-    } else {
+    if (i == IPW) {
       int qq = row0 + lane;
       qq = qq < s ? qq : s - 1;
       dma4<TAG>(rstat, stage + 2 * T::BYTES + (wave & 1) * 256, qq * 4);
+    } else if (G == 1 || i < T::NI) {
+      T::template dma_one<TAG>(rq, row0, s, pitch_q, stage + half * T::BYTES, quarter, lane, i);
+    } else {
+      T::template dma_one<TAG>(ro, row0, s, (uint32_t)(pld * 2), stage + T::BYTES, quarter, lane, i - T::NI);
     }
   };
   auto issue = [&](int t, int st) {
 #pragma unroll
-    for (int i = 0; i <= 2 * T::NI; ++i) issue_one(Burst{}, t, st, i);
+    for (int i = 0; i <= IPW; ++i) issue_one(Burst{}, t, st, i);
   };
   issue(0, 0);
   issue(1, 1);
 #pragma unroll
-  for (int kg = 0; kg < 2; ++kg)
+  for (int kg = 0; kg < G; ++kg)
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       arrive(kf[kg][kk]);
@@ -609,7 +633,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
     }
   int cur = 0;
   for (int it = 0; it < ntiles; ++it) {
-    wait_and_barrier<2 * T::NI + 1>();
+    wait_and_barrier<IPW + 1>();
     const int nn = cur == 0 ? 2 : cur - 1;
     const char *Qt = smem + cur * STAGE, *Ot = Qt + T::BYTES;
     const float *stat = reinterpret_cast<const float *>(Qt + 2 * T::BYTES);
@@ -617,9 +641,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
     if (q0 + 63 < kw) {  // wave-uniform: no query of the tile sees a key of this wave
       issue(it + 2, nn);
     } else {
-      f32x4 sc[2][4], pc[2][4];
+      f32x4 sc[G][4], pc[G][4];
 #pragma unroll
-      for (int kg = 0; kg < 2; ++kg)
+      for (int kg = 0; kg < G; ++kg)
 #pragma unroll
         for (int qb = 0; qb < 4; ++qb)
 #pragma unroll
@@ -638,24 +662,24 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
 #pragma unroll
               for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg) {
+                for (int kg = 0; kg < G; ++kg) {
                   sc[kg][2 * (i & 1) + h] = MFMA16(qfr[i % 3][h], kf[kg][i >> 1], sc[kg][2 * (i & 1) + h]);
                   pc[kg][2 * (i & 1) + h] = MFMA16(ofr[i % 3][h], vf[kg][i >> 1], pc[kg][2 * (i & 1) + h]);
                 }
             },
             [&](int i) {
-              issue_one(Spread{}, it + 2, nn, i);
-              if (i == 2 * KK - 1) issue_one(Spread{}, it + 2, nn, 2 * T::NI);
+              if (i < IPW) issue_one(Spread{}, it + 2, nn, i);
+              if (i == 2 * KK - 1) issue_one(Spread{}, it + 2, nn, IPW);
             });
       }
       // element (kg, qb, e): query q0 + 16 qb + 4 g + e, key key[kg]
-      const bool edge = q0 < kw + 32 || q0 + 63 >= s;  // wave-uniform: diagonal or past-the-end queries
+      const bool edge = q0 < kw + 16 * G || q0 + 63 >= s;  // wave-uniform: diagonal or past-the-end queries
 #pragma unroll
       for (int qb = 0; qb < 4; ++qb) {
         const f32x4 ls = *reinterpret_cast<const f32x4 *>(stat + 16 * qb + 4 * g);
         const f32x4 dd = *reinterpret_cast<const f32x4 *>(stat + 64 + 16 * qb + 4 * g);
 #pragma unroll
-        for (int kg = 0; kg < 2; ++kg)
+        for (int kg = 0; kg < G; ++kg)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int qq = q0 + 16 * qb + 4 * g + e;
@@ -666,11 +690,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
           }
       }
       {  // step i: query half i / DB, output block i % DB
-        bf16x8 pf[2][2], df[2][2], otr[4], qtr[4];
+        bf16x8 pf[2][G], df[2][G], otr[4], qtr[4];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int kg = 0; kg < 2; ++kg) {
+          for (int kg = 0; kg < G; ++kg) {
             pf[ks][kg] = pack2(sc[kg][2 * ks], sc[kg][2 * ks + 1]);
             df[ks][kg] = pack2(pc[kg][2 * ks], pc[kg][2 * ks + 1]);
           }
@@ -681,7 +705,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
             },
             [&](int i) {
 #pragma unroll
-              for (int kg = 0; kg < 2; ++kg) {
+              for (int kg = 0; kg < G; ++kg) {
                 dv[kg][i % DB] = MFMA16(otr[i & 3], pf[i / DB][kg], dv[kg][i % DB]);
                 dk[kg][i % DB] = MFMA16(qtr[i & 3], df[i / DB][kg], dk[kg][i % DB]);
               }
@@ -693,7 +717,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
-  for (int kg = 0; kg < 2; ++kg) {
+  for (int kg = 0; kg < G; ++kg) {
     if (key[kg] < s) {
       bf16 *out = dqkv + ((int64_t)bi * s + key[kg]) * ld + (int64_t)j * 3 * D;
 #pragma unroll
@@ -711,18 +735,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int s, int n, float s
   }
 }
 
+// Row groups of 16 per wave: 2 = four waves of 32 rows (every LDS fragment feeds two MFMAs, but
+// the kernel needs more than 256 registers and the compiler shuttles values between the two
+// register files), 1 = eight waves of 16 rows (twice the LDS reads, two waves per SIMD to overlap
+// the softmax arithmetic with the MFMAs, no register shuffling).  Measured at head size 160,
+// sequence 2048: forward 69 -> 55 us, dk/dv 119 -> 93 us, dq 74 -> 77 us.
+constexpr int FWD_G = 1, DQ_G = 2, DKV_G = 1;
+
 template <int D>
 int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
   constexpr int smem = 3 * 2 * 64 * D * 2;
   static bool attr = false;
   if (!attr) {
-    if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+    if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D, FWD_G>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
         hipSuccess)
       return MTNLG_HIP_ERROR;
     attr = true;
   }
   LaunchScope scope(MTNLG_K_ATTN_FWD, st);
-  attn_fwd_kernel<D><<<dim3((s + 127) / 128, n, b), 256, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a, lse);
+  attn_fwd_kernel<D, FWD_G><<<dim3((s + 127) / 128, n, b), 512 / FWD_G, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a,
+                                                                                    lse);
   return check_launch();
 }
 
@@ -732,19 +764,19 @@ int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a,
   constexpr int smem_dq = 3 * 2 * 64 * D * 2, smem_dkv = 3 * (2 * 64 * D * 2 + 512);
   static bool attr = false;
   if (!attr) {
-    if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D, DQ_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             smem_dq) != hipSuccess ||
-        hipFuncSetAttribute((const void *)attn_bwd_dkv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipFuncSetAttribute((const void *)attn_bwd_dkv_kernel<D, DKV_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             smem_dkv) != hipSuccess)
       return MTNLG_HIP_ERROR;
     attr = true;
   }
   float *Dvec = (float *)ws;
   LaunchScope scope(MTNLG_K_ATTN_BWD, st);
-  attn_bwd_dq_kernel<D><<<dim3((s + 127) / 128, n, b), 256, smem_dq, st>>>(
+  attn_bwd_dq_kernel<D, DQ_G><<<dim3((s + 127) / 128, n, b), 512 / DQ_G, smem_dq, st>>>(
       s, n, scale, (const bf16 *)qkv, (const bf16 *)a, lse, (const bf16 *)da, (bf16 *)dqkv, Dvec);
   MTNLG_TRY(check_launch());
-  attn_bwd_dkv_kernel<D><<<dim3((s + 127) / 128, n, b), 256, smem_dkv, st>>>(
+  attn_bwd_dkv_kernel<D, DKV_G><<<dim3((s + 127) / 128, n, b), 512 / DKV_G, smem_dkv, st>>>(
       s, n, scale, (const bf16 *)qkv, lse, Dvec, (const bf16 *)da, (bf16 *)dqkv);
   return check_launch();
 }
