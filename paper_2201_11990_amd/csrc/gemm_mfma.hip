@@ -435,7 +435,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 //   workgroup barrier per slab sits before the last phase (whose fragments are already in
 //   registers) so that the first fragment reads of the next slab hide behind a phase of MFMAs.
 //   Aligned problems only: M, N multiples of 256, K of 64.
-template <bool AT, bool BT>
+template <bool AT, bool BT, bool PLAIN16>
 __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NWAVES = WGM * WGN;
@@ -613,7 +613,47 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   // 128 x 64 tile, 64 rows at a time, through a private 64 x 68-float LDS patch (16-byte stores,
   // conflict-free at that pitch) into 8-column row segments, so that every global access is 16
   // bytes of a row and a wave instruction covers whole 128-byte lines.
-  {
+  if (PLAIN16 && part_id < 0) {
+    // bf16 output with at most a bias: round before the transposition, which halves the LDS
+    // traffic of the patch and leaves the second half of the epilogue a plain 16-byte copy.
+    // Patch = 64 rows x 128 B per wave, 16-byte unit u of row r at unit position u ^ ((r >> 1) & 7)
+    // (8-byte block stores and 16-byte row reads both conflict-free).
+    char *patch = smem + wave * 8192;
+    const int g4 = lane >> 4;
+    f32x4 bias4[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bias4[j][e] = 0.0f;
+      if (g.ea.flags & MTNLG_EPI_BIAS) {
+        const bf16x4 bv = *reinterpret_cast<const bf16x4 *>(static_cast<const bf16 *>(g.ea.bias) + n0 + wn * WN + j * 16 + 4 * g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias4[j][e] = (float)bv[e];
+      }
+    }
+    bf16 *cbase = static_cast<bf16 *>(g.C) + (m0 + wm * WM) * g.ldc + n0 + wn * WN;
+#pragma unroll
+    for (int p = 0; p < TM / 4; ++p) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int row = (lane & 15) + i * 16, unit = 2 * j + (g4 >> 1);
+          bf16x4 h;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) h[e] = (bf16)(acc[p * 4 + i][j][e] + bias4[j][e]);
+          *reinterpret_cast<bf16x4 *>(patch + row * 128 + ((unit ^ ((row >> 1) & 7)) << 4) + (g4 & 1) * 8) = h;
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int row = t * 8 + (lane >> 3), cv = lane & 7;   // 8 rows x 8 segments per instruction
+        const bf16x8 o = *reinterpret_cast<const bf16x8 *>(patch + row * 128 + ((cv ^ ((row >> 1) & 7)) << 4));
+        *reinterpret_cast<bf16x8 *>(cbase + (int64_t)(p * 64 + row) * g.ldc + cv * 8) = o;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // patch is rewritten by the next pass
+    }
+  } else {
     constexpr int PITCH = WN + 4;
     float *patch = reinterpret_cast<float *>(smem) + wave * (64 * PITCH);
 #pragma unroll
@@ -723,12 +763,18 @@ int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
       constexpr int stream_smem = 5 * 256 * BK * 2;
       static bool stream_attr_set = false;
       if (!stream_attr_set) {
-        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT>,
+        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess)
           return MTNLG_HIP_ERROR;
         stream_attr_set = true;
       }
-      gemm_stream_kernel<AT, BT><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
+      // bf16 output with nothing but an optional bias: the epilogue that rounds before it transposes
+      if ((g.ea.flags & ~(uint32_t)MTNLG_EPI_BIAS) == 0)
+        gemm_stream_kernel<AT, BT, true><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
+      else
+        gemm_stream_kernel<AT, BT, false><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
       MTNLG_TRY(check_launch());
       if (split) {
         splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
