@@ -238,11 +238,6 @@ int mtnlg_colsum(int dtype, int64_t T, int64_t C, const void *in, void *out, int
 /* out = res + partial + bias[col] over [T,h] (bias nullable). */
 int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const void *partial,
                         const void *bias, void *out, void *stream);
-/* out[c,r] = in[r,c] for a row-major [R,C] matrix (bf16 only; R and C multiples of 64, else
- * MTNLG_UNSUPPORTED_SHAPE).  The weight-gradient GEMMs (Megatron's dW = dY^T X, the backward of
- * the column/row-parallel linears of Section 2.1's tensor slicing) use it to make the upstream
- * gradient contiguous along the token axis they contract over.  in and out must not overlap. */
-int mtnlg_transpose(int dtype, int64_t R, int64_t C, const void *in, void *out, void *stream);
 
 /* --- per-kernel-class timing (optional) --------------------------------------
  * While enabled, the library brackets each kernel launch with HIP events on the

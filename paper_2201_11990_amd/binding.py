@@ -92,7 +92,6 @@ def lib():
             "mtnlg_colsum_workspace": (sz, [i64, i64]),
             "mtnlg_colsum": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp]),
             "mtnlg_bias_residual": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]),
-            "mtnlg_transpose": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp]),
             "mtnlg_profile_enable": (ctypes.c_int, [ctypes.c_int]),
             "mtnlg_profile_read": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]),
         }
@@ -108,7 +107,7 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
-            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_transpose", "mtnlg_profile_enable",
+            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_profile_enable",
             "mtnlg_profile_read")
 
 
@@ -322,11 +321,6 @@ def mtnlg_bias_residual(res, partial, bias, out):
     T, h = res.shape
     _check(lib().mtnlg_bias_residual(_dtype_code(res), T, h, _p(res), _p(partial), _p(bias), _p(out), _stream()),
            "mtnlg_bias_residual")
-
-
-def mtnlg_transpose(inp, out):
-    R, C = inp.shape
-    _check(lib().mtnlg_transpose(_dtype_code(inp), R, C, _p(inp), _p(out), _stream()), "mtnlg_transpose")
 
 
 def mtnlg_profile_enable(on):

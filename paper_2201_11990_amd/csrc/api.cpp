@@ -75,7 +75,7 @@ void saved_layout(const Shape &S, mtnlg_saved_layout *L) {
 
 // Scratch carved from the caller's workspace.
 struct Work {
-  size_t dgz, du, dx1, da, dqkv, red, attn, ping, pong, gemm, gemm_bytes, tr, total;
+  size_t dgz, du, dx1, da, dqkv, red, attn, ping, pong, gemm, gemm_bytes, total;
 };
 
 void work_layout(const Shape &S, Work *W) {
@@ -104,10 +104,6 @@ void work_layout(const Shape &S, Work *W) {
   }
   W->gemm_bytes = gw;
   W->gemm = c.take(gw);
-  // transposed upstream gradient of the weight-gradient GEMMs (the widest of dy, dz, dx1, dqkv)
-  int64_t widest = S.h > S.F ? S.h : S.F;
-  if (3 * S.p > widest) widest = 3 * S.p;
-  W->tr = c.take(S.T * widest * S.es);
   W->total = c.off;
 }
 
@@ -179,21 +175,6 @@ int layer_fwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
   return MTNLG_OK;
 }
 
-// Weight gradient dW[Nout, Kin] = dY^T X with dY [T, Nout], X [T, Kin].  Both operands are
-// row-contiguous for this contraction over T, the most expensive form for the matrix-core
-// kernel (every fragment needs transposing LDS reads).  On aligned bf16 problems dY is first
-// transposed (an HBM-bound pass over T x Nout elements), which turns the product into
-// dYt[Nout, T] X[T, Kin] with a K-contiguous left operand; timed under the weight-gradient class.
-int wgrad_gemm(const Shape &S, int64_t Nout, int64_t Kin, const void *dY, const void *X, void *dW, uint32_t epi,
-               void *tr, void *gws, size_t gws_bytes, hipStream_t st) {
-  if (S.dtype == MTNLG_BF16 && S.T % 64 == 0 && gemm_mfma_streams(Nout, Kin, S.T)) {
-    MTNLG_TRY(transpose_bf16(S.T, Nout, dY, tr, st));
-    return gemm_mfma_bf16(MTNLG_GEMM_NN, Nout, Kin, S.T, tr, X, dW, nullptr, nullptr, epi, gws, gws_bytes, st,
-                          MTNLG_K_GEMM_TN);
-  }
-  return mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, Nout, Kin, S.T, dY, X, dW, nullptr, nullptr, epi, gws, gws_bytes, st);
-}
-
 int layer_bwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, const void *saved,
                    const void *dy, void *dx, const mtnlg_layer_grads *G, void *ws, mtnlg_reduce_fn reduce,
                    void *user, hipStream_t st) {
@@ -207,33 +188,33 @@ int layer_bwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
   const void *u2 = at(saved, L.u2), *z = at(saved, L.z), *g = at(saved, L.g);
   const float *lse = (const float *)at(saved, L.lse);
   void *dgz = at(ws, W.dgz), *du = at(ws, W.du), *dx1 = at(ws, W.dx1), *da = at(ws, W.da);
-  void *dqkv = at(ws, W.dqkv), *red = at(ws, W.red), *attn_ws = at(ws, W.attn), *gws = at(ws, W.gemm), *tr = at(ws, W.tr);
+  void *dqkv = at(ws, W.dqkv), *red = at(ws, W.red), *attn_ws = at(ws, W.attn), *gws = at(ws, W.gemm);
   const int g32 = S.g32 ? 1 : 0, acc = S.acc ? 1 : 0;
   const uint32_t wg_epi = (S.acc ? MTNLG_EPI_ACCUMULATE : 0u) | ((S.g32 && S.dtype == MTNLG_BF16) ? MTNLG_EPI_OUT_F32 : 0u);
 
   // y = x1 + M + b2:  db2 = sum_t dy ; dg = dy W2 ; dW2 = dy^T g
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.h, dy, G->b_fc2, g32, acc, red, st));
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.F, S.h, dy, w->w_fc2, dgz, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
-  MTNLG_TRY(wgrad_gemm(S, S.h, S.F, dy, g, G->w_fc2, wg_epi, tr, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.F, S.T, dy, g, G->w_fc2, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   // dz = dg o GeLU'(z) ; db1 = sum_t dz
   MTNLG_TRY(mtnlg_gelu_bwd(S.dtype, S.gelu_erf, S.T * S.F, z, dgz, dgz, st));
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.F, dgz, G->b_fc1, g32, acc, red, st));
   // du2_r = dz W1 ; dW1 = dz^T u2
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, S.F, dgz, w->w_fc1, du, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
-  MTNLG_TRY(wgrad_gemm(S, S.F, S.h, dgz, u2, G->w_fc1, wg_epi, tr, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.F, S.h, S.T, dgz, u2, G->w_fc1, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   MTNLG_TRY(call_reduce(reduce, user, du, (size_t)(S.T * S.h), S.dtype, st));
   // dx1 = dy + LN2^T(du2) ; dgamma2, dbeta2 ; dbo = sum_t dx1
   MTNLG_TRY(mtnlg_layernorm_bwd(S.dtype, S.T, S.h, x1, w->ln2_g, mu2, rs2, du, dy, dx1, G->ln2_g, G->ln2_b,
                                 G->b_o, g32, acc, red, st));
   // da = dx1 Wo ; dWo = dx1^T a
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.p, S.h, dx1, w->w_o, da, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
-  MTNLG_TRY(wgrad_gemm(S, S.h, S.p, dx1, a, G->w_o, wg_epi, tr, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.p, S.T, dx1, a, G->w_o, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   // attention backward
   MTNLG_TRY(mtnlg_attention_bwd(S.dtype, S.b, S.s, S.n, S.d, S.scale, qkv, a, lse, da, dqkv, attn_ws, st));
   // dbqkv = sum_t dqkv ; du1_r = dqkv Wqkv ; dWqkv = dqkv^T u1
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, 3 * S.p, dqkv, G->b_qkv, g32, acc, red, st));
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, 3 * S.p, dqkv, w->w_qkv, du, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
-  MTNLG_TRY(wgrad_gemm(S, 3 * S.p, S.h, dqkv, u1, G->w_qkv, wg_epi, tr, gws, W.gemm_bytes, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, 3 * S.p, S.h, S.T, dqkv, u1, G->w_qkv, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
   MTNLG_TRY(call_reduce(reduce, user, du, (size_t)(S.T * S.h), S.dtype, st));
   // dx = dx1 + LN1^T(du1) ; dgamma1, dbeta1
   MTNLG_TRY(mtnlg_layernorm_bwd(S.dtype, S.T, S.h, x, w->ln1_g, mu1, rs1, du, dx1, dx, G->ln1_g, G->ln1_b,

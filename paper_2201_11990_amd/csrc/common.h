@@ -172,8 +172,6 @@ int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, c
                    hipStream_t stream, int prof_class = -1);
 // true when the problem takes the streaming kernel (aligned M, N, K)
 bool gemm_mfma_streams(int64_t M, int64_t N, int64_t K);
-// out[c][r] = in[r][c], bf16, R and C multiples of 64
-int transpose_bf16(int64_t R, int64_t C, const void *in, void *out, hipStream_t stream);
 size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int attention_fwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
                          void *a, float *lse, hipStream_t stream);

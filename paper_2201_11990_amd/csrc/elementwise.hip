@@ -428,36 +428,6 @@ static unsigned ew_grid(int64_t nvec) {
 
 using namespace mtnlg;
 
-// ---- bf16 matrix transpose -------------------------------------------------------------
-// out[c][r] = in[r][c] for an R x C row-major matrix, 64 x 64 tiles through LDS.  A thread
-// loads 8 columns of two adjacent rows (2 x 16 B), packs the two rows' values of each column
-// into one 4-byte word -- two neighbours of a transposed row -- and stores it at
-// word (column, row pair) of a [64][33]-word tile (the odd pitch keeps the stores free of bank
-// conflicts); rows of the transposed tile leave as 16-byte global stores.
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(int64_t R, int64_t C, const bf16 *__restrict__ in,
-                                                             bf16 *__restrict__ out) {
-  __shared__ uint32_t tile[64 * 33];
-  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
-  const int t = threadIdx.x, cc = t & 7, rp = t >> 3;   // 8 column chunks x 32 row pairs
-  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-  const u32x4 lo = *reinterpret_cast<const u32x4 *>(in + (r0 + 2 * rp) * C + c0 + 8 * cc);
-  const u32x4 hi = *reinterpret_cast<const u32x4 *>(in + (r0 + 2 * rp + 1) * C + c0 + 8 * cc);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t a = (lo[j >> 1] >> (16 * (j & 1))) & 0xFFFFu, b = (hi[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-    tile[(8 * cc + j) * 33 + rp] = a | (b << 16);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = (t >> 3) + 32 * i, ch = t & 7;   // transposed row c, 16-byte chunk ch
-    u32x4 v;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) v[w] = tile[c * 33 + 4 * ch + w];
-    *reinterpret_cast<u32x4 *>(out + (c0 + c) * R + r0 + 8 * ch) = v;
-  }
-}
-
 extern "C" {
 
 int mtnlg_layernorm_fwd(int dtype, int64_t T, int64_t h, const void *x, const void *partial,
@@ -566,19 +536,7 @@ int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const 
   return check_launch();
 }
 
-int mtnlg_transpose(int dtype, int64_t R, int64_t C, const void *in, void *out, void *stream) {
-  if (dtype != MTNLG_BF16) return MTNLG_UNSUPPORTED_SHAPE;
-  return transpose_bf16(R, C, in, out, (hipStream_t)stream);
-}
-
 }  // extern "C"
 
 namespace mtnlg {
-int transpose_bf16(int64_t R, int64_t C, const void *in, void *out, hipStream_t st) {
-  if (!in || !out) return MTNLG_NULL_POINTER;
-  if (R <= 0 || C <= 0 || R % 64 || C % 64) return MTNLG_UNSUPPORTED_SHAPE;
-  LaunchScope scope(MTNLG_K_ELEMENTWISE, st);
-  transpose_bf16_kernel<<<dim3((unsigned)(C / 64), (unsigned)(R / 64)), 256, 0, st>>>(R, C, (const bf16 *)in, (bf16 *)out);
-  return check_launch();
-}
 }  // namespace mtnlg

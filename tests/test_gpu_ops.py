@@ -149,7 +149,8 @@ def test_layernorm_fwd_bwd(dtype, T, h):
     assert_close(dx, o_dx, tol, "ln dx without residual")
 
 
-ATT_CASES = [(2, 40, 3, 64), (1, 130, 2, 128), (2, 77, 2, 160), (1, 1, 1, 8), (1, 300, 1, 32), (1, 257, 2, 160)]
+ATT_CASES = [(2, 40, 3, 64), (1, 130, 2, 128), (2, 77, 2, 160), (1, 1, 1, 8), (1, 300, 1, 32), (1, 257, 2, 160),
+             (1, 700, 2, 160), (1, 520, 1, 64), (2, 390, 1, 128)]   # many streamed tiles: the three-stage ring wraps
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
@@ -211,15 +212,3 @@ def test_gelu_colsum_bias_residual(dtype):
     assert_close(out, to_np(res) + to_np(part), tol, "residual")
 
 
-@pytest.mark.gpu
-@pytest.mark.parametrize("R,C", [(64, 64), (128, 320), (2048, 7680), (192, 20480)])
-def test_transpose_is_exact(R, C):
-    g = torch.Generator(device="cuda").manual_seed(R + C)
-    a = torch.randn((R, C), generator=g, device="cuda").bfloat16()
-    out = torch.full((C, R), float("nan"), dtype=torch.bfloat16, device="cuda")
-    M.mtnlg_transpose(a, out)
-    torch.cuda.synchronize()
-    # a transpose moves bytes: compare bit patterns with the strided view
-    assert torch.equal(out.view(torch.int16), a.t().contiguous().view(torch.int16))
-    with pytest.raises(M.MtnlgError):
-        M.mtnlg_transpose(a[:, :C - 8].contiguous(), torch.empty((C - 8, R), dtype=torch.bfloat16, device="cuda"))
