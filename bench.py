@@ -54,6 +54,27 @@ def cpu_baseline(wl, weights0, x, prefix):
                       f"weights), {fl / 1e9:.1f} GFLOP in {dt:.1f} s"}
 
 
+# kernel symbol of each GEMM class in the rocprofv3 summaries (template arguments: A transposed, B transposed)
+CLASS_SYMBOL = {"gemm_nt": "gemm_stream_kernel<false, false", "gemm_nn": "gemm_stream_kernel<false, true",
+                "gemm_tn": "gemm_stream_kernel<true, true"}
+
+
+def counter_traffic(cls):
+    """HBM-side bytes per launch of a GEMM class (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of
+    known size) from the committed summary of the two rocprofv3 --pmc runs of this benchmark; None when the
+    summary is missing.  Counters cannot be read from inside the timed run."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "stage_step_mtnlg_tp8_hbm_traffic.txt")
+    try:
+        line = [l for l in open(path) if l.startswith("TRAFFIC_TABLE ")][0]
+        table = json.loads(line[len("TRAFFIC_TABLE "):])
+    except (OSError, IndexError, ValueError):
+        return None
+    rows = [v for k, v in table.items() if k.startswith(CLASS_SYMBOL[cls])]
+    n = sum(r["launches"] for r in rows)
+    return int(sum(r["launches"] * r["bytes_per_launch"] for r in rows) / n) if n else None
+
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,8 +158,9 @@ def main():
         for k in gf:
             classes[k]["tflops"] = round(gf[k] / (prof[k][1] / args.steps * 1e-3) / 1e12, 1)
         ach = gf[dom] / (prof[dom][1] / args.steps * 1e-3) / 1e12
+        traffic = counter_traffic(dom)
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS,
-                           "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                            "all_gemm_tflops": round(sum(gf.values()) / (g_ms * 1e-3) / 1e12, 1),
                            "gemm_share_of_step": round(g_ms / ms, 3)}
         out["kernel_classes"] = classes
