@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="before the timed steps, run one plain device copy of BYTES (a known-size kernel to "
                          "calibrate FETCH_SIZE / WRITE_SIZE counters against)")
+    ap.add_argument("--micro-batches", type=int, default=1, metavar="K",
+                    help="a step = K micro-batches through mtnlg_stage_step_accumulate with fp32 gradient buffers "
+                         "(gradient accumulation); default 1 = the plain step the metric is quoted on")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
     args = ap.parse_args()
@@ -108,10 +111,22 @@ def main():
     dev = "cuda"
     weights = [make_layer_params(wl, l, seed=0, device=dev) for l in range(wl.n_layers)]
     x, dy = make_activations(wl, seed=0, device=dev)
-    run = StageRunner(wl, weights, device=dev)
+    if args.micro_batches > 1:
+        from paper_2201_11990_amd import binding as B
+        run = StageRunner(wl, weights, flags=B.WGRAD_FP32, device=dev)
+        xs = torch.stack([make_activations(wl, seed=m, device=dev)[0] for m in range(args.micro_batches)])
+        dys = torch.stack([make_activations(wl, seed=m, device=dev)[1] for m in range(args.micro_batches)])
+
+        def one_step():
+            run.step_accumulate(xs, dys)
+    else:
+        run = StageRunner(wl, weights, device=dev)
+
+        def one_step():
+            run.step(x, dy)
 
     for _ in range(args.warmup):
-        run.step(x, dy)
+        one_step()
     torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device=dev).fill_(1)
@@ -124,7 +139,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run.step(x, dy)
+        one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = None
@@ -133,7 +148,7 @@ def main():
         M.mtnlg_profile_enable(False)
 
     ms = dt / args.steps * 1e3
-    model = flops.step_model_flops(wl, "causal")
+    model = flops.step_model_flops(wl, "causal") * args.micro_batches
     value = model / (ms * 1e-3) / 1e12
     out = {
         "metric": "model TFLOP/s per GPU, MT-NLG TP=8-slice layer fwd+bwd; % of bf16 MFMA peak",
@@ -142,13 +157,14 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "hidden": wl.hidden, "heads_local": wl.heads, "head_dim": wl.head_dim,
                    "ffn_local": wl.ffn, "seq": wl.seq, "micro_batch": wl.micro_batch, "n_layers": wl.n_layers,
-                   "tp_size": wl.tp_size, "recompute": wl.recompute, "parallelism": "one GPU's TP slice, no collectives"},
+                   "tp_size": wl.tp_size, "recompute": wl.recompute, "micro_batches_per_step": args.micro_batches,
+                   "parallelism": "one GPU's TP slice, no collectives"},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
-        "model_tflops_paper_convention": round(flops.step_model_flops(wl, "full") / (ms * 1e-3) / 1e12, 2),
-        "hardware_tflops": round(flops.step_hardware_flops(wl, "causal") / (ms * 1e-3) / 1e12, 2),
+        "model_tflops_paper_convention": round(args.micro_batches * flops.step_model_flops(wl, "full") / (ms * 1e-3) / 1e12, 2),
+        "hardware_tflops": round(args.micro_batches * flops.step_hardware_flops(wl, "causal") / (ms * 1e-3) / 1e12, 2),
     }
     if prof is not None:
-        gf = gemm_flops_per_step(wl)
+        gf = {k: v * args.micro_batches for k, v in gemm_flops_per_step(wl).items()}
         classes = {}
         for k, (n, tms) in prof.items():
             if n:

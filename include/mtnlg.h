@@ -171,6 +171,21 @@ int mtnlg_stage_step(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_lay
                      void *workspace, size_t workspace_bytes, mtnlg_reduce_fn reduce, void *user,
                      void *stream);
 
+/* The same step over n_micro micro-batches with the parameter gradients summed over them -- the
+ * gradient accumulation of Section 2.1 (memory-efficient training) as one pipeline rank sees it in the
+ * steady state of the 1F1B schedule of Section 2.2: micro-batch 0 overwrites the gradient buffers
+ * (adds to them if desc carries MTNLG_ACCUMULATE_WGRAD), the following ones add.  With bf16 gradient
+ * buffers every addition rounds; MTNLG_WGRAD_FP32 gives the fp32 buffers the paper accumulates in.
+ *   x_in, dy_out in, y_out, dx_in out: [n_micro][T,h], micro-batches contiguous one after the other.
+ *   saved and workspace are those of one micro-batch and are reused by each (the activations of a
+ *   micro-batch are dead once its backward has run).  Other arguments, ownership and errors as
+ *   mtnlg_stage_step; n_micro <= 0 is MTNLG_INVALID_ARG. */
+int mtnlg_stage_step_accumulate(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_layer_weights *w,
+                                int n_micro, const void *x_in, const void *dy_out, void *y_out, void *dx_in,
+                                const mtnlg_layer_grads *grads, void *saved, size_t saved_bytes,
+                                void *workspace, size_t workspace_bytes, mtnlg_reduce_fn reduce, void *user,
+                                void *stream);
+
 /* --- single operations of the path (used by stage/layer calls; exported so each
  *     kernel can be checked and timed alone) ----------------------------------- */
 

@@ -78,6 +78,8 @@ def lib():
             "mtnlg_layer_bwd": (ctypes.c_int, [dp, pp, vp, vp, vp, vp, pp, vp, sz, REDUCE_FN, vp, vp]),
             "mtnlg_stage_step": (ctypes.c_int, [dp, ctypes.c_int, pp, vp, vp, vp, vp, pp, vp, sz, vp, sz,
                                                 REDUCE_FN, vp, vp]),
+            "mtnlg_stage_step_accumulate": (ctypes.c_int, [dp, ctypes.c_int, pp, ctypes.c_int, vp, vp, vp, vp, pp, vp,
+                                                           sz, vp, sz, REDUCE_FN, vp, vp]),
             "mtnlg_gemm_workspace": (sz, [ctypes.c_int, ctypes.c_int, i64, i64, i64]),
             "mtnlg_gemm": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, u32, vp, sz, vp]),
             "mtnlg_layernorm_fwd": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]),
@@ -104,7 +106,7 @@ def lib():
 
 EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "mtnlg_saved_layout_get",
             "mtnlg_saved_bytes", "mtnlg_stage_saved_bytes", "mtnlg_workspace_bytes", "mtnlg_layer_fwd",
-            "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
+            "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_stage_step_accumulate", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
             "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_profile_enable",
@@ -243,6 +245,20 @@ def mtnlg_stage_step(desc, weights, x_in, dy_out, y_out, dx_in, grads, saved, wo
     _check(lib().mtnlg_stage_step(ctypes.byref(a.desc), a.n_layers, a.w, _p(x_in), _p(dy_out), _p(y_out),
                                   _p(dx_in), a.g, _p(saved), _nbytes(saved), _p(workspace),
                                   _nbytes(workspace), hook, None, _stream()), "mtnlg_stage_step")
+
+
+def mtnlg_stage_step_accumulate(desc, weights, x_in, dy_out, y_out, dx_in, grads, saved, workspace, reduce=None,
+                                args=None):
+    """x_in, dy_out, y_out, dx_in: [n_micro, b, s, h] contiguous."""
+    a = args if args is not None else StageArgs(desc, weights, grads)
+    hook = _hook(reduce)
+    n_micro = x_in.shape[0]
+    assert x_in.is_contiguous() and dy_out.is_contiguous() and y_out.is_contiguous() and dx_in.is_contiguous()
+    assert dy_out.shape[0] == n_micro and y_out.shape[0] == n_micro and dx_in.shape[0] == n_micro
+    _check(lib().mtnlg_stage_step_accumulate(ctypes.byref(a.desc), a.n_layers, a.w, n_micro, _p(x_in), _p(dy_out),
+                                             _p(y_out), _p(dx_in), a.g, _p(saved), _nbytes(saved), _p(workspace),
+                                             _nbytes(workspace), hook, None, _stream()),
+           "mtnlg_stage_step_accumulate")
 
 
 def mtnlg_gemm_workspace(dtype, layout, M, N, K):

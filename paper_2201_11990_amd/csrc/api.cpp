@@ -341,6 +341,25 @@ int mtnlg_stage_step(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_lay
   return MTNLG_OK;
 }
 
+int mtnlg_stage_step_accumulate(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_layer_weights *w,
+                                int n_micro, const void *x_in, const void *dy_out, void *y_out, void *dx_in,
+                                const mtnlg_layer_grads *grads, void *saved, size_t saved_bytes, void *workspace,
+                                size_t workspace_bytes, mtnlg_reduce_fn reduce, void *user, void *stream) {
+  Shape S;
+  MTNLG_TRY(make_shape(desc, &S));
+  if (n_micro <= 0) return MTNLG_INVALID_ARG;
+  if (!x_in || !dy_out || !y_out || !dx_in) return MTNLG_NULL_POINTER;
+  const size_t stride = (size_t)(S.T * S.h * S.es);   // one micro-batch of [T,h]
+  mtnlg_layer_desc d = *desc;
+  for (int m = 0; m < n_micro; ++m) {
+    if (m == 1) d.flags |= MTNLG_ACCUMULATE_WGRAD;
+    MTNLG_TRY(mtnlg_stage_step(&d, n_layers, w, at(x_in, m * stride), at(dy_out, m * stride), at(y_out, m * stride),
+                               at(dx_in, m * stride), grads, saved, saved_bytes, workspace, workspace_bytes, reduce,
+                               user, stream));
+  }
+  return MTNLG_OK;
+}
+
 size_t mtnlg_gemm_workspace(int dtype, int layout, int64_t M, int64_t N, int64_t K) {
   (void)layout;
   return dtype == MTNLG_BF16 ? gemm_mfma_workspace_bytes(M, N, K) : 0;

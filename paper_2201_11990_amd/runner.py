@@ -35,6 +35,13 @@ class StageRunner:
                            self.workspace, reduce=reduce, args=self.args)
         return self.y, self.dx, self.grads
 
+    def step_accumulate(self, xs, dys, reduce=None):
+        """xs, dys: [n_micro, b, s, h]; returns per-micro-batch y and dx and the summed grads."""
+        ys, dxs = torch.empty_like(xs), torch.empty_like(xs)
+        B.mtnlg_stage_step_accumulate(self.desc, self.weights, xs, dys, ys, dxs, self.grads, self.saved,
+                                      self.workspace, reduce=reduce, args=self.args)
+        return ys, dxs, self.grads
+
 
 class LayerRunner:
     """Owns the buffers of a single layer's forward and backward."""

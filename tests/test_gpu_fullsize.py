@@ -59,7 +59,11 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
     Bm = (torch.randn(b_shape, generator=g, device="cuda") * 0.05).bfloat16()
     bias = torch.randn((N,), generator=g, device="cuda").bfloat16() if epi & B.EPI_BIAS else None
     aux = torch.randn((Mm, N), generator=g, device="cuda").bfloat16() if epi & (B.EPI_RESIDUAL | B.EPI_GELU) else None
-    C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    if epi & B.EPI_ACCUMULATE:  # the micro-batch loop's weight-gradient form: fp32 buffer, added to
+        C = torch.randn((Mm, N), generator=g, device="cuda", dtype=torch.float32 if epi & B.EPI_OUT_F32 else torch.bfloat16)
+        before = C.clone()
+    else:
+        C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
     res = aux.clone() if epi & B.EPI_RESIDUAL else None
     need = M.mtnlg_gemm_workspace(B.BF16, layout, Mm, N, K)
     ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
@@ -78,6 +82,8 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
         want = oracle.gelu(want)
     if epi & B.EPI_RESIDUAL:
         want = want + to_np(res)[np.ix_(rows, cols)]
+    if epi & B.EPI_ACCUMULATE:
+        want = want + to_np(before)[np.ix_(rows, cols)]
     assert_close(C[rows][:, cols], want, TOL["bf16"], f"gemm {layout} {Mm}x{N}x{K} samples")
     assert torch.isfinite(C.float()).all()
 
@@ -90,6 +96,7 @@ FULL_GEMMS = [
     ("dqkv", B.GEMM_NN, T, H, 3 * P, 0),
     ("wfc2", B.GEMM_TN, H, F, T, 0), ("wfc1", B.GEMM_TN, F, H, T, 0), ("wproj", B.GEMM_TN, H, P, T, 0),
     ("wqkv", B.GEMM_TN, 3 * P, H, T, 0),
+    ("wfc1_accumulate_fp32", B.GEMM_TN, F, H, T, B.EPI_ACCUMULATE | B.EPI_OUT_F32),
 ]
 
 

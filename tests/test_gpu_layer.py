@@ -98,6 +98,46 @@ def test_stage_step_three_layers_with_and_without_recompute(wl):
     assert torch.equal(dx2, dx3) and all(torch.equal(grads2[0][k], grads3[0][k]) for k in PARAM_NAMES)
 
 
+@pytest.mark.parametrize("wl,flags", [(TINY.with_(n_layers=2), 0), (SMALL_BF16.with_(n_layers=2), B.WGRAD_FP32),
+                                      (SMALL_BF16.with_(n_layers=2), 0)], ids=["fp32", "bf16-fp32grads", "bf16"])
+def test_micro_batch_loop_sums_the_gradients(wl, flags):
+    """Three different micro-batches through mtnlg_stage_step_accumulate: every y / dx equals the oracle's
+    for that micro-batch, the parameter gradients equal the oracle's summed over the three; a second call
+    overwrites (no carry-over), and with MTNLG_ACCUMULATE_WGRAD in the descriptor it adds on top."""
+    n_micro = 3
+    ws = [make_layer_params(wl, l, seed=3, affine="random") for l in range(wl.n_layers)]
+    acts = [make_activations(wl, seed=10 + m) for m in range(n_micro)]
+    xs = torch.stack([a[0] for a in acts]).cuda()
+    dys = torch.stack([a[1] for a in acts]).cuda()
+    per = [stage_oracle(wl, ws, *acts[m]) for m in range(n_micro)]
+    g_sum = [{k: sum(per[m][2][l][k] for m in range(n_micro)) for k in PARAM_NAMES} for l in range(wl.n_layers)]
+    tol = TOL[wl.dtype] * (1.0 if wl.dtype == "fp32" else 1.5)
+    gtol = tol if (wl.dtype == "fp32" or flags & B.WGRAD_FP32) else 2 * tol   # bf16 buffers round at every add
+    run = StageRunner(wl, [to_dev(w) for w in ws], flags=flags)
+    for _ in range(2):
+        ys, dxs, grads = run.step_accumulate(xs, dys)
+        for m in range(n_micro):
+            assert_close(ys[m], per[m][0], tol, f"y of micro-batch {m}")
+            assert_close(dxs[m], per[m][1], tol, f"dx of micro-batch {m}")
+        for l in range(wl.n_layers):
+            for name in PARAM_NAMES:
+                assert_close(grads[l][name], g_sum[l][name], gtol, f"layer {l} summed grad {name}")
+    # one micro-batch through the loop is the plain step, bit for bit
+    y1, dx1, g1 = StageRunner(wl, [to_dev(w) for w in ws], flags=flags).step(xs[0], dys[0])
+    ys, dxs, grads = run.step_accumulate(xs[:1], dys[:1])
+    assert torch.equal(ys[0], y1) and torch.equal(dxs[0], dx1)
+    assert all(torch.equal(grads[l][k], g1[l][k]) for l in range(wl.n_layers) for k in PARAM_NAMES)
+    # accumulate flag in the descriptor: the next call adds to what the buffers hold
+    acc = StageRunner(wl, [to_dev(w) for w in ws], flags=flags | B.ACCUMULATE_WGRAD)
+    acc.step_accumulate(xs, dys)
+    _, _, g2 = acc.step_accumulate(xs, dys)
+    for name in ("w_fc1", "b_qkv", "ln2_g"):
+        assert_close(g2[0][name], 2 * g_sum[0][name], 1.5 * gtol, f"twice the summed grad {name}")
+    with pytest.raises(B.MtnlgError):
+        B.mtnlg_stage_step_accumulate(run.desc, run.weights, xs[:0], dys[:0], xs[:0].clone(), xs[:0].clone(), run.grads,
+                                      run.saved, run.workspace)
+
+
 def test_stage_step_equals_chained_layer_calls():
     wl = SMALL_BF16.with_(n_layers=2)
     ws = [to_dev(make_layer_params(wl, l, seed=1, affine="random")) for l in range(2)]
