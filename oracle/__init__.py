@@ -16,6 +16,7 @@ import os
 import numpy as np
 
 from . import build as _build
+from .optimizer import adam_step, clip_coefficient, grad_sqnorm  # noqa: F401  (optimizer step, numpy)
 
 _PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")

@@ -391,3 +391,61 @@ def test_linear_pieces_match_numpy_matmul():
     dW, db = oracle.linear_wgrad(do, x)
     np.testing.assert_allclose(dW, do.T @ x, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(db, do.sum(0), rtol=1e-12, atol=1e-12)
+
+
+# ---- optimizer step (Section 3.2: Adam, beta2 = 0.95, clipping at 1.0, weight decay 0.1) ----------------
+
+def test_adam_oracle_against_the_library_adamw_and_clip():
+    """Five steps of the oracle against torch.optim.AdamW / clip_grad_norm_ in fp64 (an independent
+    implementation of the same published algorithm): weights and both moments."""
+    rng = np.random.default_rng(5)
+    shapes = [(7, 13), (31,), (4, 5, 3)]
+    p0 = [rng.standard_normal(s) * 0.02 for s in shapes]
+    tp = [torch.tensor(a.copy(), dtype=torch.float64, requires_grad=True) for a in p0]
+    opt = torch.optim.AdamW(tp, lr=5e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1)
+    p = [a.copy() for a in p0]
+    m = [np.zeros_like(a) for a in p0]
+    v = [np.zeros_like(a) for a in p0]
+    for step in range(1, 6):
+        g = [rng.standard_normal(s) * (3.0 if step % 2 else 0.01) for s in shapes]   # clipped and unclipped steps
+        for t, gi in zip(tp, g):
+            t.grad = torch.tensor(gi.copy(), dtype=torch.float64)
+        total = torch.nn.utils.clip_grad_norm_(tp, 1.0)
+        opt.step()
+        sq = oracle.grad_sqnorm(g)
+        assert abs(np.sqrt(sq) - float(total)) < 1e-12 * float(total)
+        coef = oracle.clip_coefficient(sq, 1.0)
+        assert (coef < 1.0) == (np.sqrt(sq) > 1.0)
+        for i in range(len(p)):
+            p[i], m[i], v[i] = oracle.adam_step(p[i], m[i], v[i], g[i], lr=5e-3, beta1=0.9, beta2=0.95, eps=1e-8,
+                                                weight_decay=0.1, step=step, clip_coef=coef)
+            st = opt.state[tp[i]]
+            np.testing.assert_allclose(p[i], tp[i].detach().numpy(), rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(m[i], st["exp_avg"].numpy(), rtol=1e-12, atol=1e-18)
+            np.testing.assert_allclose(v[i], st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-18)
+
+
+def test_adam_oracle_closed_forms():
+    g = np.array([3.0, -0.5, 1e-3, -2e-6])
+    p = np.array([0.1, -0.2, 0.3, 0.4])
+    z = np.zeros(4)
+    # first step from zero moments, no decay: the bias corrections cancel, the step is lr * g / (|g| + eps)
+    p1, m1, v1 = oracle.adam_step(p, z, z, g, lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=1)
+    np.testing.assert_allclose(p1, p - 1e-2 * g / (np.abs(g) + 1e-8), rtol=1e-13)
+    np.testing.assert_allclose(m1, 0.1 * g, rtol=1e-13)
+    np.testing.assert_allclose(v1, 0.05 * g * g, rtol=1e-13)
+    # zero gradient: only the decoupled decay acts, p shrinks by the factor 1 - lr * wd, moments stay zero
+    p2, m2, v2 = oracle.adam_step(p, z, z, z, lr=1e-2, weight_decay=0.1, step=7)
+    np.testing.assert_allclose(p2, p * (1 - 1e-3), rtol=1e-13)
+    assert not m2.any() and not v2.any()
+    # a constant gradient held for many steps: both corrected moments tend to g and g^2
+    pm, mm, vm = p, z, z
+    for t in range(1, 400):
+        pm, mm, vm = oracle.adam_step(pm, mm, vm, g, lr=0.0, weight_decay=0.0, step=t)
+    np.testing.assert_allclose(mm, g, rtol=1e-10)
+    np.testing.assert_allclose(vm, g * g, rtol=1e-8)
+    # clipping: below the threshold nothing changes, above it the clipped gradients have norm max_norm
+    assert oracle.clip_coefficient(0.25, 1.0) == 1.0 and oracle.clip_coefficient(123.0, 0.0) == 1.0
+    big = np.array([3.0, 4.0])
+    c = oracle.clip_coefficient(oracle.grad_sqnorm([big]), 1.0)
+    assert abs(np.linalg.norm(big * c) - 1.0) < 1e-6
