@@ -54,6 +54,41 @@ def cpu_baseline(wl, weights0, x, prefix):
                       f"weights), {fl / 1e9:.1f} GFLOP in {dt:.1f} s"}
 
 
+def optimizer_step_bench(weights, reps=3):
+    """Adam step over every parameter of the stage: one squared-norm pass over the fp32 gradients (4 B read per
+    parameter), then the fused update (16 B read, 14 B written per parameter: fp32 weight and both moments in
+    place, bf16 weight out).  Reports achieved HBM bandwidth on those algorithmic bytes."""
+    import torch
+
+    import paper_2201_11990_amd as M
+
+    tensors = [t for w in weights for t in w.values()]
+    n = sum(t.numel() for t in tensors)
+    state = [(t.float().contiguous(), torch.zeros(t.shape, device=t.device), torch.zeros(t.shape, device=t.device),
+              torch.randn(t.shape, device=t.device) * 1e-3) for t in tensors]
+    ws = torch.empty(M.mtnlg_grad_sqnorm_workspace(), dtype=torch.uint8, device=tensors[0].device)
+    sq = torch.zeros(1, device=tensors[0].device)
+
+    def step(t):
+        for i, (_, _, _, g) in enumerate(state):
+            M.mtnlg_grad_sqnorm(g, ws, sq, accumulate=i > 0)
+        for w16, (p, m, v, g) in zip(tensors, state):
+            M.mtnlg_adam_step(p, m, v, g, w16, sq, lr=5e-5, step=t, weight_decay=0.1 if w16.dim() > 1 else 0.0)
+
+    step(1)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for r in range(reps):
+        step(2 + r)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    gbs = n * 34 / (ms * 1e-3) / 1e9
+    return {"parameters": n, "ms": round(ms, 3), "bytes_per_parameter": 34, "achieved": round(gbs, 1), "peak": 8000.0,
+            "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "bound": "hbm"}
+
+
 # kernel symbol of each GEMM class in the rocprofv3 summaries (template arguments: A transposed, B transposed)
 CLASS_SYMBOL = {"gemm_nt": "gemm_stream_kernel<false, false", "gemm_nn": "gemm_stream_kernel<false, true",
                 "gemm_tn": "gemm_stream_kernel<true, true"}
@@ -89,6 +124,9 @@ def main():
     ap.add_argument("--micro-batches", type=int, default=1, metavar="K",
                     help="a step = K micro-batches through mtnlg_stage_step_accumulate with fp32 gradient buffers "
                          "(gradient accumulation); default 1 = the plain step the metric is quoted on")
+    ap.add_argument("--optimizer-step", action="store_true",
+                    help="also time the Adam step (squared gradient norm + fused update) over all parameters of the "
+                         "stage and add an `optimizer_step` object (HBM roofline) to the line")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
     args = ap.parse_args()
@@ -183,6 +221,9 @@ def main():
     else:
         out["roofline"] = {"bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": None, "traffic": None}
+    if args.optimizer_step:
+        del run
+        out["optimizer_step"] = optimizer_step_bench(weights)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, weights[0], x, args.cpu_prefix)
     print(json.dumps(out))

@@ -254,6 +254,39 @@ int mtnlg_colsum(int dtype, int64_t T, int64_t C, const void *in, void *out, int
 int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const void *partial,
                         const void *bias, void *out, void *stream);
 
+/* --- optimizer step on the slice (Section 3.2: Adam, beta1 0.9, beta2 0.95, epsilon 1e-8, gradient
+ *     norm clipped at 1.0, weight decay 0.1; Section 2.1: fp32 copies of weights and gradients and the
+ *     two Adam states, 20 bytes per parameter).  Works on the fp32 gradient buffers that
+ *     MTNLG_WGRAD_FP32 makes the backward pass accumulate into. ------------------------------------- */
+
+typedef struct {
+  float lr;            /* learning rate of this step (warm-up and decay are the caller's)            */
+  float beta1, beta2;  /* decay rates of the two moments, in [0,1)                                   */
+  float eps;           /* added to the root of the second moment, > 0                                */
+  float weight_decay;  /* decoupled: lr * weight_decay * weight is subtracted; 0 for tensors that    */
+                       /* do not decay                                                               */
+  float max_grad_norm; /* clip the global gradient norm at this value; <= 0: no clipping             */
+  int32_t step;        /* update count t, from 1, for the bias corrections 1 - beta^t                */
+} mtnlg_adam_desc;
+
+/* sqnorm[0] (device float) = sum of squares of grad[0..count), or that added to sqnorm[0] when
+ * accumulate != 0 (one scalar over several tensors).  Deterministic: fixed ranges, fixed summation
+ * tree, fp64 partial sums.  Across ranks the scalars are summed by the caller before mtnlg_adam_step.
+ * grad 16-byte aligned; workspace >= mtnlg_grad_sqnorm_workspace() bytes, 8-byte aligned. */
+size_t mtnlg_grad_sqnorm_workspace(void);
+int mtnlg_grad_sqnorm(int64_t count, const float *grad, void *workspace, float *sqnorm, int accumulate,
+                      void *stream);
+/* One Adam update of `count` parameters, in place on the fp32 weight `master` and the moments m, v:
+ *   g' = grad * min(1, max_grad_norm / (sqrt(sqnorm[0]) + 1e-6));  m = beta1 m + (1-beta1) g';
+ *   v = beta2 v + (1-beta2) g'^2;  master -= lr * ((m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps)
+ *   + weight_decay * master);  weight_bf16 (nullable) = master rounded to nearest even.
+ * sqnorm: device scalar holding the squared global gradient norm (NULL: no clipping); it is read on the
+ * device, nothing synchronises with the host.  All fp32 pointers 16-byte aligned, weight_bf16 8-byte.
+ * grad is not modified.  Errors: MTNLG_NULL_POINTER, MTNLG_INVALID_ARG (count <= 0, step < 1, rates
+ * out of range, alignment), MTNLG_HIP_ERROR. */
+int mtnlg_adam_step(const mtnlg_adam_desc *desc, int64_t count, float *master, float *m, float *v,
+                    const float *grad, void *weight_bf16, const float *sqnorm, void *stream);
+
 /* --- per-kernel-class timing (optional) --------------------------------------
  * While enabled, the library brackets each kernel launch with HIP events on the
  * launch stream.  mtnlg_profile_read synchronises those events and returns, per

@@ -40,6 +40,11 @@ class LayerDesc(ctypes.Structure):
                 ("flags", ctypes.c_uint32)]
 
 
+class AdamDesc(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("max_grad_norm", ctypes.c_float), ("step", ctypes.c_int32)]
+
+
 class _Ptrs12(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
 
@@ -80,6 +85,9 @@ def lib():
                                                 REDUCE_FN, vp, vp]),
             "mtnlg_stage_step_accumulate": (ctypes.c_int, [dp, ctypes.c_int, pp, ctypes.c_int, vp, vp, vp, vp, pp, vp,
                                                            sz, vp, sz, REDUCE_FN, vp, vp]),
+            "mtnlg_grad_sqnorm_workspace": (sz, []),
+            "mtnlg_grad_sqnorm": (ctypes.c_int, [i64, vp, vp, vp, ctypes.c_int, vp]),
+            "mtnlg_adam_step": (ctypes.c_int, [ctypes.POINTER(AdamDesc), i64, vp, vp, vp, vp, vp, vp, vp]),
             "mtnlg_gemm_workspace": (sz, [ctypes.c_int, ctypes.c_int, i64, i64, i64]),
             "mtnlg_gemm": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, u32, vp, sz, vp]),
             "mtnlg_layernorm_fwd": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]),
@@ -109,7 +117,8 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_stage_step_accumulate", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
-            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_profile_enable",
+            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
+            "mtnlg_profile_enable",
             "mtnlg_profile_read")
 
 
@@ -337,6 +346,29 @@ def mtnlg_bias_residual(res, partial, bias, out):
     T, h = res.shape
     _check(lib().mtnlg_bias_residual(_dtype_code(res), T, h, _p(res), _p(partial), _p(bias), _p(out), _stream()),
            "mtnlg_bias_residual")
+
+
+def mtnlg_grad_sqnorm_workspace():
+    return lib().mtnlg_grad_sqnorm_workspace()
+
+
+def mtnlg_grad_sqnorm(grad, workspace, sqnorm, accumulate=False):
+    """grad: fp32 tensor (any shape, contiguous); sqnorm: fp32 device tensor of one element."""
+    assert grad.dtype == torch.float32 and grad.is_contiguous() and sqnorm.dtype == torch.float32
+    _check(lib().mtnlg_grad_sqnorm(grad.numel(), _p(grad), _p(workspace), _p(sqnorm), int(bool(accumulate)), _stream()),
+           "mtnlg_grad_sqnorm")
+
+
+def mtnlg_adam_step(master, m, v, grad, weight_bf16=None, sqnorm=None, *, lr, step, beta1=0.9, beta2=0.95, eps=1e-8,
+                    weight_decay=0.1, max_grad_norm=1.0):
+    """In-place Adam update of fp32 tensors master, m, v from fp32 grad; weight_bf16 receives the rounded weight."""
+    for t in (master, m, v, grad):
+        assert t.dtype == torch.float32 and t.is_contiguous() and t.numel() == master.numel()
+    if weight_bf16 is not None:
+        assert weight_bf16.dtype == torch.bfloat16 and weight_bf16.is_contiguous() and weight_bf16.numel() == master.numel()
+    d = AdamDesc(lr, beta1, beta2, eps, weight_decay, max_grad_norm, step)
+    _check(lib().mtnlg_adam_step(ctypes.byref(d), master.numel(), _p(master), _p(m), _p(v), _p(grad), _p(weight_bf16),
+                                 _p(sqnorm), _stream()), "mtnlg_adam_step")
 
 
 def mtnlg_profile_enable(on):

@@ -212,3 +212,55 @@ def test_gelu_colsum_bias_residual(dtype):
     assert_close(out, to_np(res) + to_np(part), tol, "residual")
 
 
+
+
+# ---- optimizer step (Section 3.2: Adam, clipping, weight decay; Section 2.1: fp32 copies and states) ----------
+
+@pytest.mark.parametrize("count", [1, 1023, 4096 + 3, 3_000_001])
+def test_adam_step_against_the_oracle(count):
+    """Three updates of a slice: squared gradient norm (two tensors summed into one scalar), clipped and
+    unclipped steps, decaying and non-decaying tensors.  fp32 arithmetic against the fp64 oracle: 2e-6 relative
+    on weights and moments; the bf16 weight is exactly the rounded fp32 weight."""
+    g = torch.Generator(device="cuda").manual_seed(count)
+    p = (torch.randn(count, generator=g, device="cuda") * 0.02).contiguous()
+    m, v = torch.zeros_like(p), torch.zeros_like(p)
+    w16 = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    other = torch.randn(777, generator=g, device="cuda") * 0.01      # a second tensor of the "model"
+    ws = torch.empty(M.mtnlg_grad_sqnorm_workspace(), dtype=torch.uint8, device="cuda")
+    sq = torch.full((1,), float("nan"), device="cuda")
+    po, mo, vo = to_np(p), to_np(m), to_np(v)
+    for step in range(1, 4):
+        scale = 5.0 if step != 2 else 1e-3 / math.sqrt(count)          # steps 1, 3 clip; step 2 does not
+        grad = (torch.randn(count, generator=g, device="cuda") * scale).contiguous()
+        wd = 0.1 if step != 3 else 0.0
+        M.mtnlg_grad_sqnorm(grad, ws, sq)
+        M.mtnlg_grad_sqnorm(other, ws, sq, accumulate=True)
+        want_sq = oracle.grad_sqnorm([to_np(grad), to_np(other)])
+        assert abs(float(sq) - want_sq) <= 1e-6 * want_sq
+        coef = oracle.clip_coefficient(want_sq, 1.0)
+        assert (coef < 1.0) == (step != 2)
+        M.mtnlg_adam_step(p, m, v, grad, w16, sq, lr=5e-3, step=step, weight_decay=wd)
+        po, mo, vo = oracle.adam_step(po, mo, vo, to_np(grad), lr=5e-3, beta1=0.9, beta2=0.95, eps=1e-8,
+                                      weight_decay=wd, step=step, clip_coef=coef)
+        for name, got, want in (("weight", p, po), ("m", m, mo), ("v", v, vo)):
+            err = np.abs(to_np(got) - want).max()
+            assert err <= 2e-6 * np.abs(want).max() + 1e-30, (name, step, err)
+        assert torch.equal(w16, p.to(torch.bfloat16)), "bf16 weight is the rounded fp32 weight"
+    # without the scalar (or with max_grad_norm <= 0) nothing is clipped
+    p2, m2, v2 = p.clone(), m.clone(), v.clone()
+    big = torch.full((count,), 100.0, device="cuda")
+    M.mtnlg_adam_step(p2, m2, v2, big, None, None, lr=1e-3, step=4)
+    pw, mw, vw = oracle.adam_step(to_np(p), to_np(m), to_np(v), to_np(big), lr=1e-3, step=4)
+    assert np.abs(to_np(m2) - mw).max() <= 2e-6 * np.abs(mw).max()
+    assert np.abs(to_np(p2) - pw).max() <= 2e-6 * np.abs(pw).max()
+
+
+def test_adam_step_rejects_bad_arguments():
+    p = torch.zeros(64, device="cuda")
+    with pytest.raises(B.MtnlgError):
+        M.mtnlg_adam_step(p, p.clone(), p.clone(), p.clone(), lr=1e-3, step=0)
+    with pytest.raises(B.MtnlgError):
+        M.mtnlg_adam_step(p, p.clone(), p.clone(), p.clone(), lr=1e-3, step=1, beta2=1.0)
+    with pytest.raises(B.MtnlgError):   # misaligned fp32 pointer
+        M.mtnlg_adam_step(torch.zeros(33, device="cuda")[1:], torch.zeros(32, device="cuda"),
+                          torch.zeros(32, device="cuda"), torch.zeros(32, device="cuda"), lr=1e-3, step=1)
