@@ -316,3 +316,7 @@ def stage_step(dims, weights, x, dy):
     for l in reversed(range(len(weights))):
         g, grads[l] = layer_bwd(dims, weights[l], xs[l], saves[l], g)
     return xs[-1], g, grads
+
+
+from .head import (cross_entropy_bwd, cross_entropy_fwd, embedding_bwd, embedding_fwd,  # noqa: E402,F401
+                   lm_head_step)

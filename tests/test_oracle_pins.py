@@ -449,3 +449,85 @@ def test_adam_oracle_closed_forms():
     big = np.array([3.0, 4.0])
     c = oracle.clip_coefficient(oracle.grad_sqnorm([big]), 1.0)
     assert abs(np.linalg.norm(big * c) - 1.0) < 1e-6
+
+
+# ---- first / last stage extras (GPT-2 readings: tied embedding, final LayerNorm, next-token cross-entropy) --------
+
+def _head_case(rng, T=24, h=16, V=40, seq=8):
+    x = rng.standard_normal((T, h))
+    gamma, beta = rng.standard_normal(h) * 0.5 + 1.0, rng.standard_normal(h) * 0.1
+    E = rng.standard_normal((V, h)) * 0.3
+    targets = rng.integers(0, V, T)
+    dloss = rng.uniform(0.2, 1.5, T)
+    return x, gamma, beta, E, targets, dloss
+
+
+def test_lm_head_oracle_against_library_autograd():
+    rng = np.random.default_rng(11)
+    x, gamma, beta, E, targets, dloss = _head_case(rng)
+    loss, dx, dg, db, dE = oracle.lm_head_step(x, gamma, beta, E, targets, dloss)
+    tx, tg, tb, tE = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, gamma, beta, E))
+    u = Fnn.layer_norm(tx, (x.shape[1],), tg, tb, 1e-5)
+    tl = Fnn.cross_entropy(u @ tE.T, torch.tensor(targets), reduction="none")
+    (tl * torch.tensor(dloss)).sum().backward()
+    np.testing.assert_allclose(loss, tl.detach().numpy(), rtol=1e-12)
+    for got, want in ((dx, tx.grad), (dg, tg.grad), (db, tb.grad), (dE, tE.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-9, atol=1e-13)
+    # a uniform row: loss = log V whatever the target
+    l0, _, _ = oracle.cross_entropy_fwd(np.zeros((3, 40)), [0, 7, 39])
+    np.testing.assert_allclose(l0, np.log(40.0), rtol=1e-14)
+    # softmax minus one-hot: every gradient row of the unsliced loss sums to zero
+    lg = rng.standard_normal((5, 9))
+    tg5 = [1, 2, 3, 4, 8]
+    _, m5, s5 = oracle.cross_entropy_fwd(lg, tg5)
+    d = oracle.cross_entropy_bwd(lg, tg5, m5, s5, np.ones(5))
+    assert np.abs(d.sum(axis=1)).max() < 1e-14 and all(d[t, tg5[t]] < 0 for t in range(5))
+
+
+def test_vocabulary_slices_reproduce_the_unsliced_head_and_embedding():
+    """Four ranks, each with a quarter of E's rows, exchanging one maximum and three sums, give the unsliced loss,
+    dx and LayerNorm gradients, and each its own rows of dE; likewise for the embedding lookup."""
+    rng = np.random.default_rng(12)
+    x, gamma, beta, E, targets, dloss = _head_case(rng)
+    V, R = E.shape[0], 4
+    Vl = V // R
+    want = oracle.lm_head_step(x, gamma, beta, E, targets, dloss)
+
+    # lock-step emulation of the exchanges: run every rank up to each exchange point by re-running with recorded values
+    logits = [oracle.linear_fwd(oracle.layernorm_fwd(x, gamma, beta)[0], E[r * Vl:(r + 1) * Vl]) for r in range(R)]
+    m = np.max([l.max(1) for l in logits], axis=0)
+    s = sum(np.exp(l - m[:, None]).sum(1) for l in logits)
+    tl = sum(np.array([l[t, targets[t] - r * Vl] if r * Vl <= targets[t] < (r + 1) * Vl else 0.0
+                       for t in range(len(targets))]) for r, l in enumerate(logits))
+    dus = [oracle.linear_dgrad(oracle.cross_entropy_bwd(logits[r], targets, m, s, dloss, r * Vl), E[r * Vl:(r + 1) * Vl])
+           for r in range(R)]
+    du = sum(dus)
+
+    def make_reduce(state):
+        def reduce(a, op):
+            state["n"] += 1
+            return {1: m, 2: s, 3: tl, 4: du}[state["n"]]
+        return reduce
+    for r in range(R):
+        got = oracle.lm_head_step(x, gamma, beta, E[r * Vl:(r + 1) * Vl], targets, dloss, vocab_start=r * Vl,
+                                  reduce=make_reduce({"n": 0}))
+        for g, w in zip(got[:4], want[:4]):
+            np.testing.assert_allclose(g, w, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(got[4], want[4][r * Vl:(r + 1) * Vl], rtol=1e-10, atol=1e-13)
+
+    # embedding: lookup against the library routine, slices sum to it, gradients against autograd
+    seq, T, h = 8, 24, E.shape[1]
+    tokens = rng.integers(0, V, T)
+    P = rng.standard_normal((seq, h))
+    xe = oracle.embedding_fwd(tokens, E, P, seq)
+    tE, tP = torch.tensor(E, requires_grad=True), torch.tensor(P, requires_grad=True)
+    te = Fnn.embedding(torch.tensor(tokens), tE) + tP.repeat(T // seq, 1)
+    np.testing.assert_allclose(xe, te.detach().numpy(), rtol=1e-15)
+    parts = [oracle.embedding_fwd(tokens, E[r * Vl:(r + 1) * Vl], np.zeros_like(P), seq, r * Vl) for r in range(R)]
+    np.testing.assert_allclose(sum(parts) + np.tile(P, (T // seq, 1)), xe, rtol=1e-15)
+    dxe = rng.standard_normal((T, h))
+    (te * torch.tensor(dxe)).sum().backward()
+    for r in range(R):
+        dE_r, dP = oracle.embedding_bwd(tokens, dxe, Vl, seq, r * Vl)
+        np.testing.assert_allclose(dE_r, tE.grad.numpy()[r * Vl:(r + 1) * Vl], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(dP, tP.grad.numpy(), rtol=1e-12, atol=1e-15)
