@@ -54,6 +54,45 @@ def cpu_baseline(wl, weights0, x, prefix):
                       f"weights), {fl / 1e9:.1f} GFLOP in {dt:.1f} s"}
 
 
+def lm_head_bench(wl, vocab_local=6400, reps=10):
+    """mtnlg_lm_head_step at the slice's shape: T tokens, hidden h, 6400 rows of the tied embedding (GPT-2's
+    vocabulary padded to 51200, one of 8 slices; the paper gives no vocabulary size).  FLOPs = the three GEMMs
+    (logits, dgrad, wgrad), 6 T V h."""
+    import torch
+
+    import paper_2201_11990_amd as M
+    from paper_2201_11990_amd import binding as B
+
+    T, h = wl.tokens, wl.hidden
+    dev = "cuda"
+    x = torch.randn((T, h), device=dev).bfloat16()
+    gamma, beta = torch.ones(h, device=dev).bfloat16(), torch.zeros(h, device=dev).bfloat16()
+    E = (torch.randn((vocab_local, h), device=dev) * 0.004).bfloat16()
+    targets = torch.randint(0, vocab_local, (T,), device=dev, dtype=torch.int32)
+    desc = B.head_desc(h, vocab_local, 0, wl.seq, wl.micro_batch, "bf16")
+    ws = torch.empty(M.mtnlg_lm_head_workspace(desc), dtype=torch.uint8, device=dev)
+    loss = torch.empty(T, device=dev)
+    dx, dg, db, dE = torch.empty_like(x), torch.empty_like(gamma), torch.empty_like(beta), torch.empty_like(E)
+
+    def step():
+        M.mtnlg_lm_head_step(desc, x, gamma, beta, E, targets, None, loss, dx, dg, db, dE, ws)
+
+    step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    fl = 6.0 * T * vocab_local * h
+    return {"tokens": T, "hidden": h, "vocab_local": vocab_local, "ms": round(ms, 3),
+            "achieved": round(fl / (ms * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "bound": "mfma",
+            "mean_loss": round(float(loss.mean()), 4)}
+
+
 def optimizer_step_bench(weights, reps=3):
     """Adam step over every parameter of the stage: one squared-norm pass over the fp32 gradients (4 B read per
     parameter), then the fused update (16 B read, 14 B written per parameter: fp32 weight and both moments in
@@ -124,6 +163,9 @@ def main():
     ap.add_argument("--micro-batches", type=int, default=1, metavar="K",
                     help="a step = K micro-batches through mtnlg_stage_step_accumulate with fp32 gradient buffers "
                          "(gradient accumulation); default 1 = the plain step the metric is quoted on")
+    ap.add_argument("--lm-head", action="store_true",
+                    help="also time the last stage's extras (final LayerNorm, tied output projection on a 6400-row "
+                         "vocabulary slice, cross-entropy, and back) and add an `lm_head_step` object to the line")
     ap.add_argument("--optimizer-step", action="store_true",
                     help="also time the Adam step (squared gradient norm + fused update) over all parameters of the "
                          "stage and add an `optimizer_step` object (HBM roofline) to the line")
@@ -221,6 +263,8 @@ def main():
     else:
         out["roofline"] = {"bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": None, "traffic": None}
+    if args.lm_head:
+        out["lm_head_step"] = lm_head_bench(wl)
     if args.optimizer_step:
         del run
         out["optimizer_step"] = optimizer_step_bench(weights)

@@ -254,6 +254,48 @@ int mtnlg_colsum(int dtype, int64_t T, int64_t C, const void *in, void *out, int
 int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const void *partial,
                         const void *bias, void *out, void *stream);
 
+/* --- first and last pipeline stage's extras (the paper names the GPT-2 decoder, Section 3.2, and
+ *     prints none of this: token embedding E [V,h] with learned positions P [s,h], final LayerNorm,
+ *     output projection tied to E, next-token cross-entropy).  Under the tensor slicing of
+ *     Section 2.1 a rank owns the contiguous rows [vocab_start, vocab_start + vocab_local) of E. --- */
+
+typedef struct {
+  int32_t hidden;       /* h                                                                     */
+  int32_t vocab_local;  /* rows of E on this rank (bf16 path: a multiple of 8)                   */
+  int32_t vocab_start;  /* global id of this rank's first row                                    */
+  int32_t seq, micro_batch; /* s, b; T = b * s tokens, token-major like the layer activations     */
+  int32_t dtype;        /* MTNLG_F32 or MTNLG_BF16 (storage; statistics and logits are fp32)     */
+  float ln_eps;
+} mtnlg_head_desc;
+
+enum mtnlg_reduce_op { MTNLG_REDUCE_SUM = 0, MTNLG_REDUCE_MAX = 1 };
+/* Exchange hook of a vocabulary-sliced group: replace buf[0..count) (device, element type `dtype`)
+ * by its elementwise sum or maximum over the ranks, enqueued on `stream`; return 0.  NULL = a group
+ * of one (the local values are the group's). */
+typedef int (*mtnlg_reduce_op_fn)(void *buf, size_t count, int dtype, int op, void *stream, void *user);
+
+/* x [T,h] = sum over ranks of (E[tokens[t] - vocab_start] if the id is this rank's, else 0), hook
+ * (SUM), then + P[t mod s].  tokens: device int32 [T], global ids.  emb [vocab_local,h], pos [s,h]. */
+int mtnlg_embedding_fwd(const mtnlg_head_desc *desc, const int32_t *tokens, const void *emb, const void *pos,
+                        void *x, mtnlg_reduce_op_fn reduce, void *user, void *stream);
+/* demb [vocab_local,h] = per token id of this rank, the sum (in token order: deterministic) of the
+ * rows of dx [T,h]; dpos [s,h] = dx summed over the batch.  Both overwritten, storage dtype. */
+int mtnlg_embedding_bwd(const mtnlg_head_desc *desc, const int32_t *tokens, const void *dx, void *demb,
+                        void *dpos, void *stream);
+/* Last stage, forward and backward in one call: u = LN(x); logits = u E^T (this rank's block, fp32);
+ * loss[t] = log sum_v exp(logits[t,v]) - logits[t, targets[t]] with the maximum, the sum of
+ * exponentials and the target's logit exchanged through the hook (MAX, SUM, SUM);
+ * dlogits = dloss[t] * (softmax - onehot) (dloss NULL: 1/T each, the mean loss);
+ * du = dlogits E, hook (SUM); demb = dlogits^T u; dx, d_ln_g, d_ln_b = LN backward.
+ *   x [T,h] in; targets: device int32 [T] global ids; loss: device float [T] out; dx [T,h],
+ *   d_ln_g, d_ln_b [h], demb [vocab_local,h] out (storage dtype, overwritten).
+ *   workspace >= mtnlg_lm_head_workspace(desc) bytes.  Errors as for the layer calls. */
+size_t mtnlg_lm_head_workspace(const mtnlg_head_desc *desc);
+int mtnlg_lm_head_step(const mtnlg_head_desc *desc, const void *x, const void *ln_g, const void *ln_b,
+                       const void *emb, const int32_t *targets, const float *dloss, float *loss, void *dx,
+                       void *d_ln_g, void *d_ln_b, void *demb, void *workspace, size_t workspace_bytes,
+                       mtnlg_reduce_op_fn reduce, void *user, void *stream);
+
 /* --- optimizer step on the slice (Section 3.2: Adam, beta1 0.9, beta2 0.95, epsilon 1e-8, gradient
  *     norm clipped at 1.0, weight decay 0.1; Section 2.1: fp32 copies of weights and gradients and the
  *     two Adam states, 20 bytes per parameter).  Works on the fp32 gradient buffers that

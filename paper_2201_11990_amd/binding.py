@@ -45,6 +45,17 @@ class AdamDesc(ctypes.Structure):
                 ("weight_decay", ctypes.c_float), ("max_grad_norm", ctypes.c_float), ("step", ctypes.c_int32)]
 
 
+class HeadDesc(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int32), ("vocab_local", ctypes.c_int32), ("vocab_start", ctypes.c_int32),
+                ("seq", ctypes.c_int32), ("micro_batch", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float)]
+
+
+REDUCE_OP_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                ctypes.c_void_p, ctypes.c_void_p)
+REDUCE_SUM, REDUCE_MAX = 0, 1
+
+
 class _Ptrs12(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
 
@@ -85,6 +96,11 @@ def lib():
                                                 REDUCE_FN, vp, vp]),
             "mtnlg_stage_step_accumulate": (ctypes.c_int, [dp, ctypes.c_int, pp, ctypes.c_int, vp, vp, vp, vp, pp, vp,
                                                            sz, vp, sz, REDUCE_FN, vp, vp]),
+            "mtnlg_lm_head_workspace": (sz, [ctypes.POINTER(HeadDesc)]),
+            "mtnlg_embedding_fwd": (ctypes.c_int, [ctypes.POINTER(HeadDesc), vp, vp, vp, vp, REDUCE_OP_FN, vp, vp]),
+            "mtnlg_embedding_bwd": (ctypes.c_int, [ctypes.POINTER(HeadDesc), vp, vp, vp, vp, vp]),
+            "mtnlg_lm_head_step": (ctypes.c_int, [ctypes.POINTER(HeadDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                  vp, sz, REDUCE_OP_FN, vp, vp]),
             "mtnlg_grad_sqnorm_workspace": (sz, []),
             "mtnlg_grad_sqnorm": (ctypes.c_int, [i64, vp, vp, vp, ctypes.c_int, vp]),
             "mtnlg_adam_step": (ctypes.c_int, [ctypes.POINTER(AdamDesc), i64, vp, vp, vp, vp, vp, vp, vp]),
@@ -118,6 +134,7 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
             "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
+            "mtnlg_lm_head_workspace", "mtnlg_embedding_fwd", "mtnlg_embedding_bwd", "mtnlg_lm_head_step",
             "mtnlg_profile_enable",
             "mtnlg_profile_read")
 
@@ -346,6 +363,59 @@ def mtnlg_bias_residual(res, partial, bias, out):
     T, h = res.shape
     _check(lib().mtnlg_bias_residual(_dtype_code(res), T, h, _p(res), _p(partial), _p(bias), _p(out), _stream()),
            "mtnlg_bias_residual")
+
+
+def head_desc(hidden, vocab_local, vocab_start, seq, micro_batch, dtype, ln_eps=1e-5):
+    return HeadDesc(hidden, vocab_local, vocab_start, seq, micro_batch, {"fp32": F32, "bf16": BF16}[dtype], ln_eps)
+
+
+def _op_hook(reduce):
+    """reduce(ptr:int, count:int, dtype:int, op:int, stream:int) -> None, or None."""
+    if reduce is None:
+        return ctypes.cast(None, REDUCE_OP_FN)
+
+    def cb(buf, count, dtype, op, stream, _user):
+        try:
+            reduce(buf, count, dtype, op, stream)
+            return 0
+        except Exception:  # noqa: BLE001 - must not unwind through C
+            return 1
+
+    return REDUCE_OP_FN(cb)
+
+
+def _copy_into_pointer(ptr, src):
+    """Copy a contiguous device tensor over the device memory at `ptr` (for exchange hooks)."""
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    rc = hip.hipMemcpyAsync(ctypes.c_void_p(ptr), ctypes.c_void_p(src.data_ptr()), _nbytes(src), 3, _stream())
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpyAsync failed: {rc}")
+    torch.cuda.current_stream().synchronize()   # src may be freed by the caller right after
+
+
+def mtnlg_lm_head_workspace(desc):
+    return lib().mtnlg_lm_head_workspace(ctypes.byref(desc))
+
+
+def mtnlg_embedding_fwd(desc, tokens, emb, pos, x, reduce=None):
+    assert tokens.dtype == torch.int32
+    _check(lib().mtnlg_embedding_fwd(ctypes.byref(desc), _p(tokens), _p(emb), _p(pos), _p(x), _op_hook(reduce), None,
+                                     _stream()), "mtnlg_embedding_fwd")
+
+
+def mtnlg_embedding_bwd(desc, tokens, dx, demb, dpos):
+    assert tokens.dtype == torch.int32
+    _check(lib().mtnlg_embedding_bwd(ctypes.byref(desc), _p(tokens), _p(dx), _p(demb), _p(dpos), _stream()),
+           "mtnlg_embedding_bwd")
+
+
+def mtnlg_lm_head_step(desc, x, ln_g, ln_b, emb, targets, dloss, loss, dx, d_ln_g, d_ln_b, demb, workspace, reduce=None):
+    assert targets.dtype == torch.int32 and loss.dtype == torch.float32
+    assert dloss is None or dloss.dtype == torch.float32
+    _check(lib().mtnlg_lm_head_step(ctypes.byref(desc), _p(x), _p(ln_g), _p(ln_b), _p(emb), _p(targets), _p(dloss),
+                                    _p(loss), _p(dx), _p(d_ln_g), _p(d_ln_b), _p(demb), _p(workspace),
+                                    _nbytes(workspace), _op_hook(reduce), None, _stream()), "mtnlg_lm_head_step")
 
 
 def mtnlg_grad_sqnorm_workspace():

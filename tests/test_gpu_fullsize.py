@@ -195,3 +195,37 @@ def test_stage_step_in_the_benchmark_configuration_is_deterministic_and_chains_l
     y3, dx3, g3 = rec.step(x, dy)
     assert torch.equal(y3, y1) and torch.equal(dx3, dx1)
     assert all(torch.equal(g3[0][k], g1[0][k]) for k in PARAM_NAMES)
+
+
+VOCAB_LOCAL = 6400   # GPT-2's 50257-entry vocabulary padded to 51200, one of 8 slices (the paper gives no size)
+
+
+def test_lm_head_at_full_width_on_a_token_prefix():
+    """With the loss weights zero beyond the first n0 tokens, loss[:n0], dx[:n0], the LayerNorm gradients and dE are
+    exactly those of the n0-token problem (token rows are independent up to the sums over tokens), which the oracle
+    computes with the full-width E slice; the GPU runs all T = 2048 tokens in the shape bench.py times."""
+    n0, T, h, Vl = 24, WL.tokens, WL.hidden, VOCAB_LOCAL
+    g = torch.Generator(device="cuda").manual_seed(7)
+    x = torch.randn((T, h), generator=g, device="cuda").bfloat16()
+    gamma = (torch.randn(h, generator=g, device="cuda") * 0.2 + 1.0).bfloat16()
+    beta = (torch.randn(h, generator=g, device="cuda") * 0.1).bfloat16()
+    E = (torch.randn((Vl, h), generator=g, device="cuda") * 0.004).bfloat16()
+    targets = torch.randint(0, Vl, (T,), generator=g, device="cuda", dtype=torch.int32)
+    dloss = torch.zeros(T, device="cuda")
+    dloss[:n0] = torch.rand(n0, generator=g, device="cuda") + 0.5
+    desc = B.head_desc(h, Vl, 0, WL.seq, WL.micro_batch, "bf16")
+    ws = torch.empty(M.mtnlg_lm_head_workspace(desc), dtype=torch.uint8, device="cuda")
+    loss = torch.empty(T, device="cuda")
+    dx, dg, db, dE = torch.empty_like(x), torch.empty_like(gamma), torch.empty_like(beta), torch.empty_like(E)
+    M.mtnlg_lm_head_step(desc, x, gamma, beta, E, targets, dloss, loss, dx, dg, db, dE, ws)
+    torch.cuda.synchronize()
+    want = oracle.lm_head_step(to_np(x[:n0]), to_np(gamma), to_np(beta), to_np(E), targets[:n0].cpu().numpy(),
+                               to_np(dloss[:n0]))
+    assert np.abs(to_np(loss[:n0]) - want[0]).max() <= 3e-2
+    assert torch.isfinite(loss).all() and (loss > 0).all()
+    tol = TOL["bf16"] * 1.5
+    assert_close(dx[:n0], want[1], tol, "dx[:n0]")
+    assert (dx[n0:] == 0).all(), "tokens with zero loss weight get exactly zero gradient"
+    assert_close(dg, want[2], tol, "dgamma")
+    assert_close(db, want[3], tol, "dbeta")
+    assert_close(dE, want[4], tol, "dE")

@@ -289,3 +289,113 @@ def test_profile_counts_every_kernel_class():
     assert all(ms >= 0 for _, ms in prof.values()) and prof["gemm_nt"][1] > 0
     run.forward(x)  # disabled again: still works
     torch.cuda.synchronize()
+
+
+# ---- first / last stage extras ------------------------------------------------------------------------------
+
+def _head_inputs(dtype, T, h, V, seed):
+    g = torch.Generator().manual_seed(seed)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    x = torch.randn((T, h), generator=g).to(tdt)
+    gamma = (torch.randn(h, generator=g) * 0.3 + 1.0).to(tdt)
+    beta = (torch.randn(h, generator=g) * 0.1).to(tdt)
+    E = (torch.randn((V, h), generator=g) * 0.05).to(tdt)
+    targets = torch.randint(0, V, (T,), generator=g, dtype=torch.int32)
+    dloss = torch.rand(T, generator=g) * 1.5 + 0.2
+    return x, gamma, beta, E, targets, dloss
+
+
+def _run_head(desc, x, gamma, beta, E, targets, dloss, reduce=None):
+    T, h = x.shape
+    ws = torch.empty(M.mtnlg_lm_head_workspace(desc), dtype=torch.uint8, device="cuda")
+    loss = torch.full((T,), float("nan"), device="cuda")
+    dx = torch.full_like(x, float("nan"), device="cuda")
+    dg, db = torch.empty_like(gamma, device="cuda"), torch.empty_like(beta, device="cuda")
+    dE = torch.full_like(E, float("nan"), device="cuda")
+    M.mtnlg_lm_head_step(desc, x.cuda(), gamma.cuda(), beta.cuda(), E.cuda(), targets.cuda(),
+                         None if dloss is None else dloss.cuda(), loss, dx, dg, db, dE, ws, reduce=reduce)
+    return loss, dx, dg, db, dE
+
+
+@pytest.mark.parametrize("dtype,b,s,h,V", [("fp32", 2, 12, 136, 50), ("fp32", 1, 33, 64, 1000), ("bf16", 2, 75, 264, 520),
+                                           ("bf16", 1, 256, 512, 1536)])
+def test_lm_head_step_against_the_oracle(dtype, b, s, h, V):
+    T = b * s
+    x, gamma, beta, E, targets, dloss = _head_inputs(dtype, T, h, V, seed=V + s)
+    desc = B.head_desc(h, V, 0, s, b, dtype)
+    tol = TOL[dtype] * (1.0 if dtype == "fp32" else 1.5)
+    for dl in (dloss, None):
+        want = oracle.lm_head_step(to_np(x), to_np(gamma), to_np(beta), to_np(E), to_np(targets),
+                                   to_np(dl) if dl is not None else np.full(T, 1.0 / T))
+        got = _run_head(desc, x, gamma, beta, E, targets, dl)
+        # the loss is a difference of O(log V) terms: absolute tolerance on it, relative on the gradients
+        assert np.abs(to_np(got[0]) - want[0]).max() <= (2e-5 if dtype == "fp32" else 3e-2)
+        for name, gt, wt in zip(("dx", "dgamma", "dbeta", "dE"), got[1:], want[1:]):
+            assert_close(gt, wt, tol, f"lm head {name}")
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_vocabulary_sliced_head_exchanges_one_maximum_and_three_sums(dtype):
+    """Two ranks with half of E's rows each; the hook hands every rank the group's value at the four exchange
+    points (computed by the oracle), in the order MAX, SUM, SUM, SUM.  Each rank then returns the unsliced loss,
+    dx, LayerNorm gradients and its own rows of dE."""
+    b, s, h, V, R = 2, 40, 264, 512, 2
+    T, Vl = b * s, V // R
+    x, gamma, beta, E, targets, dloss = _head_inputs(dtype, T, h, V, seed=3)
+    xn, gn, bn, En, dn = (to_np(a) for a in (x, gamma, beta, E, dloss))
+    tn = targets.numpy().astype(np.int64)
+    want = oracle.lm_head_step(xn, gn, bn, En, tn, dn)
+    u = oracle.layernorm_fwd(xn, gn, bn)[0]
+    logits = oracle.linear_fwd(u, En)
+    m = logits.max(1)
+    ssum = np.exp(logits - m[:, None]).sum(1)
+    tl = logits[np.arange(T), tn]
+    du = oracle.linear_dgrad(oracle.cross_entropy_bwd(logits, tn, m, ssum, dn), En)
+    group = [(B.REDUCE_MAX, m), (B.REDUCE_SUM, ssum), (B.REDUCE_SUM, tl), (B.REDUCE_SUM, du)]
+    tol = TOL[dtype] * (1.0 if dtype == "fp32" else 1.5)
+    for r in range(R):
+        calls = []
+
+        def hook(ptr, count, dt, op, stream, calls=calls):
+            k = len(calls)
+            want_op, value = group[k]
+            assert op == want_op and count == value.size
+            tdt = torch.float32 if dt == B.F32 else torch.bfloat16
+            calls.append(k)
+            # write the group's value over the library's buffer
+            src = torch.tensor(value, dtype=torch.float64).to(tdt).reshape(-1).cuda()
+            B._copy_into_pointer(ptr, src)
+        desc = B.head_desc(h, Vl, r * Vl, s, b, dtype)
+        got = _run_head(desc, x, gamma, beta, E[r * Vl:(r + 1) * Vl].contiguous(), targets, dloss, reduce=hook)
+        assert len(calls) == 4
+        assert np.abs(to_np(got[0]) - want[0]).max() <= (2e-5 if dtype == "fp32" else 3e-2)
+        for name, gt, wt in zip(("dx", "dgamma", "dbeta"), got[1:4], want[1:4]):
+            assert_close(gt, wt, tol, f"rank {r} {name}")
+        assert_close(got[4], want[4][r * Vl:(r + 1) * Vl], tol, f"rank {r} its rows of dE")
+
+
+@pytest.mark.parametrize("dtype,b,s,h,V,vs", [("fp32", 2, 9, 136, 37, 10), ("bf16", 3, 50, 2056, 64, 100), ("bf16", 1, 128, 264, 304, 0)])
+def test_embedding_lookup_and_its_gradient(dtype, b, s, h, V, vs):
+    """Tokens drawn from a range wider than this rank's rows [vs, vs + V): foreign ids give zero rows forward and
+    no gradient backward; repeated ids sum."""
+    T = b * s
+    g = torch.Generator().manual_seed(h + V)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    E = (torch.randn((V, h), generator=g) * 0.1).to(tdt)
+    P = (torch.randn((s, h), generator=g) * 0.1).to(tdt)
+    tokens = torch.randint(max(0, vs - 5), vs + V + 5, (T,), generator=g, dtype=torch.int32)
+    tokens[:3] = vs + 1   # a repeated id
+    desc = B.head_desc(h, V, vs, s, b, dtype)
+    x = torch.full((T, h), float("nan"), dtype=tdt, device="cuda")
+    M.mtnlg_embedding_fwd(desc, tokens.cuda(), E.cuda(), P.cuda(), x)
+    assert_close(x, oracle.embedding_fwd(to_np(tokens), to_np(E), to_np(P), s, vs), TOL[dtype], "embedding")
+    dx = torch.randn((T, h), generator=g).to(tdt)
+    dE = torch.full((V, h), float("nan"), dtype=tdt, device="cuda")
+    dP = torch.full((s, h), float("nan"), dtype=tdt, device="cuda")
+    M.mtnlg_embedding_bwd(desc, tokens.cuda(), dx.cuda(), dE, dP)
+    dE_o, dP_o = oracle.embedding_bwd(to_np(tokens), to_np(dx), V, s, vs)
+    assert_close(dE, dE_o, TOL[dtype], "dE")
+    assert_close(dP, dP_o, TOL[dtype], "dP")
+    dE2 = torch.empty_like(dE)
+    M.mtnlg_embedding_bwd(desc, tokens.cuda(), dx.cuda(), dE2, dP)
+    assert torch.equal(dE, dE2), "fixed summation order"
