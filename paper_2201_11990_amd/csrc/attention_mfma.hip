@@ -46,17 +46,20 @@ constexpr float kLn2 = 0.6931471805599453f;
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // A 64-row x D-column bf16 tile in LDS, rows as in memory, the 16-byte units of a row
-// permuted by an XOR that depends on the row so that both kinds of fragment read are free
-// of bank conflicts (checked by enumeration for the three head sizes).
+// permuted by an XOR that depends on the row.  The masks are the ones a micro-benchmark of the
+// two fragment read patterns found fastest (cycles per wave instruction, two waves per SIMD):
+// head size 160: 4.5-4.9 for the 16-byte reads and 3.0 for the transposing reads (no conflicts);
+// 64: the same; 128: 4.5 and 4.0 (no mask of this form is conflict-free for both at a row of
+// exactly 256 bytes).  The masks look at the low four bits of the row only.
 template <int D>
 struct Tile {
   static constexpr int UPR = D / 8;        // 16-byte units per row
   static constexpr int BYTES = 64 * D * 2;
   static constexpr int NI = D / 32;        // DMA instructions per wave and tile (16 rows)
   static __device__ __forceinline__ int mask(int row) {
-    if constexpr (D == 160) return ((row >> 2) & 1) * 2 + ((row >> 3) & 1);
-    else if constexpr (D == 128) return ((row & 7) << 1) | ((row >> 3) & 1);
-    else return (((row >> 1) & 3) << 1) | ((row >> 3) & 1);
+    if constexpr (D == 160) return (row >> 1) & 3;
+    else if constexpr (D == 128) return row & 15;
+    else return row & 7;
   }
   static __device__ __forceinline__ int off(int row, int u) { return (row * UPR + (u ^ mask(row))) * 16; }
 

@@ -425,7 +425,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 //   from HBM for the first time: the weights); the DMA instructions of a slab are spread over
 //   the four phases of a slab (two per phase and wave) so that the texture path never sees a burst.
 //   K-contiguous operand: stage = [256 rows][128 B], 16-byte chunk c of row r at chunk position
-//     c ^ (r & 7) ^ ((r >> 3) & 7); MFMA fragments are 16-byte LDS reads.
+//     c ^ (r & 7); MFMA fragments are 16-byte LDS reads (this placement measured conflict-free for the
+//     fragment pattern -- 16 rows x one chunk per 16 lanes -- at 4.5-4.9 cycles per wave instruction;
+//     with a further ^ (r >> 3), which a model of 16 consecutive lanes per LDS pass asks for, the
+//     same reads take 7.8).
 //   Row-contiguous operand ([k][row] in memory): stage = [64 k][512 B] as in memory, with the
 //     16-byte unit u of k-row k at unit position (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
 //     MFMA fragments are two transposing 8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   // q fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l the 16 bytes at 16 l.
   auto dma_offset = [&](int q, int64_t ld, bool transposed) -> uint32_t {
     if (!transposed) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
-      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3) ^ (q & 7);
+      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3);   // row % 8 == lane / 8
       return (uint32_t)(row * ld * 2 + c * 16);
     } else {             // k-rows 2q, 2q+1, lane l: k = 2q + l/32, unit position l%32
       const int k = 2 * q + (lane >> 5), p = lane & 31;
@@ -516,7 +519,7 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   auto frag = [&](const char *stage, int r0, int kk, bool transposed) -> bf16x8 {
     if (!transposed) {
       const int row = r0 + (lane & 15);
-      return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + swz(row, kk * 4 + (lane >> 4)));
+      return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + (((kk * 4 + (lane >> 4)) ^ (row & 7)) << 4));
     } else {
       // as address supplier lane 16 grp + L covers k-row kbase + L/4, rows r0 + 4 (L%4) .. + 3
       const int grp = lane >> 4, L = lane & 15;
