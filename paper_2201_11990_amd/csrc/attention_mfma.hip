@@ -742,8 +742,8 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dkv_kernel(int s, int n, flo
 // the kernel needs more than 256 registers and the compiler shuttles values between the two
 // register files), 1 = eight waves of 16 rows (twice the LDS reads, two waves per SIMD to overlap
 // the softmax arithmetic with the MFMAs, no register shuffling).  Measured at head size 160,
-// sequence 2048: forward 69 -> 55 us, dk/dv 119 -> 93 us, dq 74 -> 77 us.
-constexpr int FWD_G = 1, DQ_G = 2, DKV_G = 1;
+// sequence 2048 (2 -> 1): forward 69 -> 54 us, dk/dv 119 -> 86 us, dq 77 -> 69 us.
+constexpr int FWD_G = 1, DQ_G = 1, DKV_G = 1;
 
 template <int D>
 int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
