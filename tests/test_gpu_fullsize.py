@@ -229,3 +229,97 @@ def test_lm_head_at_full_width_on_a_token_prefix():
     assert_close(dg, want[2], tol, "dgamma")
     assert_close(db, want[3], tol, "dbeta")
     assert_close(dE, want[4], tol, "dE")
+
+
+# ---- the other named workloads at their full sizes ---------------------------------------------------------------
+
+def _prefix_inputs(wl, n0, seed=0):
+    x, dy = make_activations(wl, seed=seed, device="cuda")
+    dy[:, n0:] = 0
+    return x, dy
+
+
+def _prefix_np(t, n0):
+    """First n0 tokens of every sequence, as the oracle's [b * n0, h] fp64 array."""
+    return to_np(t[:, :n0]).reshape(t.shape[0] * n0, -1)
+
+
+def test_gpt1p3b_layer_on_causal_prefixes_of_four_sequences():
+    """1.3B-shaped unsliced layer, micro-batch 4 (T = 8192): each of the four sequences keeps only its first n0
+    upstream-gradient rows, so the oracle's b = 4, s = n0 problem fixes y[:, :n0], all of dx and every parameter
+    gradient of the full launch."""
+    wl, n0 = WORKLOADS["gpt1p3b_layer"], 96
+    w = make_layer_params(wl, 0, seed=0, device="cuda", affine="random")
+    x, dy = _prefix_inputs(wl, n0)
+    run = LayerRunner(wl, w)
+    y = run.forward(x)
+    dx, grads = run.backward(x, dy)
+    torch.cuda.synchronize()
+    small = oracle_dims(wl.with_(seq=n0))
+    wn = {k: to_np(v) for k, v in w.items()}
+    xs = _prefix_np(x, n0)
+    y_o, saved = oracle.layer_fwd(small, wn, xs)
+    dx_o, g_o = oracle.layer_bwd(small, wn, xs, saved, _prefix_np(dy, n0))
+    tol = TOL["bf16"]
+    assert_close(y[:, :n0], y_o, tol, "y[:, :n0]")
+    assert_close(dx[:, :n0], dx_o, tol, "dx[:, :n0]")
+    assert (dx[:, n0:] == 0).all()
+    for name in PARAM_NAMES:
+        assert_close(grads[name], g_o[name], tol, f"grad {name}")
+
+
+def test_recomputing_stage_at_micro_batch_four_on_causal_prefixes():
+    """Three slice layers, micro-batch 4, activations recomputed inside backward: the stage step's y, dx and the
+    36 parameter gradients against the oracle's three-layer stack on the prefixes, and bit for bit against the
+    same step with all activations kept."""
+    wl, n0 = WORKLOADS["mtnlg_tp8_stage_mb4_recompute"], 12
+    assert wl.recompute and wl.micro_batch == 4
+    ws = [make_layer_params(wl, l, seed=0, device="cuda", affine="random") for l in range(wl.n_layers)]
+    x, dy = _prefix_inputs(wl, n0)
+    rec = StageRunner(wl, ws)
+    assert rec.desc.flags & B.RECOMPUTE
+    y, dx, grads = rec.step(x, dy)
+    torch.cuda.synchronize()
+    y_o, dx_o, g_o = oracle.stage_step(oracle_dims(wl.with_(seq=n0)), [{k: to_np(v) for k, v in w.items()} for w in ws],
+                                       _prefix_np(x, n0), _prefix_np(dy, n0))
+    tol = TOL["bf16"] * 1.5  # three layers of bf16 rounding
+    assert_close(y[:, :n0], y_o, tol, "y[:, :n0]")
+    assert_close(dx[:, :n0], dx_o, tol, "dx[:, :n0]")
+    assert (dx[:, n0:] == 0).all()
+    for l in range(wl.n_layers):
+        for name in PARAM_NAMES:
+            assert_close(grads[l][name], g_o[l][name], tol, f"layer {l} grad {name}")
+    del y_o, dx_o, g_o
+    keep = StageRunner(wl.with_(recompute=False), ws)
+    assert keep.saved.numel() > rec.saved.numel()
+    y2, dx2, grads2 = keep.step(x, dy)
+    assert torch.equal(y, y2) and torch.equal(dx, dx2)
+    for l in range(wl.n_layers):
+        for name in PARAM_NAMES:
+            assert torch.equal(grads[l][name], grads2[l][name]), (l, name)
+
+
+@pytest.mark.timeout(900)
+def test_whole_unsliced_mtnlg_layer_on_a_causal_prefix():
+    """One full layer (h 20480, 128 heads x 160, FFN 81920: 5.0e9 parameters, 10 GB in bf16) on one GPU.  The oracle
+    takes the same weights in fp64 on the first n0 tokens; tensors are compared and released one at a time to bound
+    host memory (the fp64 weights alone are 40 GB)."""
+    wl, n0 = WORKLOADS["mtnlg_full_layer"], 16
+    w = make_layer_params(wl, 0, seed=0, device="cuda", affine="random")
+    x, dy = _prefix_inputs(wl, n0)
+    run = LayerRunner(wl, w)
+    y = run.forward(x)
+    dx, grads = run.backward(x, dy)
+    torch.cuda.synchronize()
+    small = oracle_dims(wl.with_(seq=n0))
+    wn = {k: to_np(v) for k, v in w.items()}
+    xs = _prefix_np(x, n0)
+    y_o, saved = oracle.layer_fwd(small, wn, xs)
+    dx_o, g_o = oracle.layer_bwd(small, wn, xs, saved, _prefix_np(dy, n0))
+    del wn, saved
+    tol = TOL["bf16"]
+    assert_close(y[:, :n0], y_o, tol, "y[:n0]")
+    assert_close(dx[:, :n0], dx_o, tol, "dx[:n0]")
+    assert (dx[:, n0:] == 0).all()
+    for name in PARAM_NAMES:
+        assert_close(grads[name], g_o.pop(name), tol, f"grad {name}")
