@@ -330,11 +330,14 @@ int mtnlg_adam_step(const mtnlg_adam_desc *desc, int64_t count, float *master, f
                     const float *grad, void *weight_bf16, const float *sqnorm, void *stream);
 
 /* --- per-kernel-class timing (optional) --------------------------------------
- * While enabled, the library brackets each kernel launch with HIP events on the
- * launch stream.  mtnlg_profile_read synchronises those events and returns, per
- * class, the number of launches and their summed duration in milliseconds, then
- * clears the record.  Event objects are host-side resources created on demand
- * and destroyed by mtnlg_profile_enable(0).  Not thread-safe. */
+ * While enabled, the library records a HIP event on the launch stream after each
+ * of its launches (and one before the first of a run); a launch is timed from the
+ * event that closed the previous launch on the same stream, so work that the
+ * caller enqueues between two library launches counts for the second.
+ * mtnlg_profile_read synchronises those events and returns, per class, the number
+ * of launches and their summed duration in milliseconds, then clears the record.
+ * Event objects are host-side resources created on demand and destroyed by
+ * mtnlg_profile_enable(0).  Not thread-safe. */
 enum mtnlg_kernel_class {
   MTNLG_K_GEMM_NT = 0, MTNLG_K_GEMM_NN, MTNLG_K_GEMM_TN, MTNLG_K_ATTN_FWD, MTNLG_K_ATTN_BWD,
   MTNLG_K_LN_FWD, MTNLG_K_LN_BWD, MTNLG_K_GELU, MTNLG_K_COLSUM, MTNLG_K_ELEMENTWISE,

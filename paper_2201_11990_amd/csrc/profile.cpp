@@ -1,40 +1,62 @@
 // Optional per-kernel-class timing with HIP events on the launch stream.
+//
+// Every scope records one event when it closes.  A scope that opens on the stream on which the previous
+// scope closed takes that event as its beginning (the two would sit back to back in the queue with the
+// same time stamp), so a run of launches costs one event each instead of two; only the first scope after
+// timing is switched on, after a read-out, or after a change of stream records a beginning of its own.
+// A scope's time therefore runs from the end of the previous scope: whatever else the caller puts on the
+// stream between two scopes is counted for the second.
 #include <vector>
 
 #include "common.h"
 
 namespace mtnlg {
 
-struct EventPair {
+struct Record {
   int cls;
-  hipEvent_t start, stop;
+  hipEvent_t begin, end;
 };
 
 static bool g_enabled = false;
-static std::vector<EventPair> g_records;
-static std::vector<EventPair> g_pool;
+static std::vector<Record> g_records;
+static std::vector<hipEvent_t> g_used;   // every event referenced by g_records, once
+static std::vector<hipEvent_t> g_pool;
+static hipEvent_t g_chain_end = nullptr;  // closing event of the latest scope, nullptr: chain broken
+static hipStream_t g_chain_stream = nullptr;
+
+static hipEvent_t take_event() {
+  hipEvent_t e = nullptr;
+  if (!g_pool.empty()) {
+    e = g_pool.back();
+    g_pool.pop_back();
+  } else if (hipEventCreate(&e) != hipSuccess) {
+    return nullptr;
+  }
+  g_used.push_back(e);
+  return e;
+}
 
 LaunchScope::LaunchScope(int cls_, hipStream_t s) : cls(cls_), stream(s), idx(-1) {
   if (!g_enabled) return;
-  EventPair ep;
-  if (!g_pool.empty()) {
-    ep = g_pool.back();
-    g_pool.pop_back();
+  Record r{cls, nullptr, nullptr};
+  if (g_chain_end && g_chain_stream == stream) {
+    r.begin = g_chain_end;
   } else {
-    if (hipEventCreate(&ep.start) != hipSuccess) return;
-    if (hipEventCreate(&ep.stop) != hipSuccess) {
-      (void)hipEventDestroy(ep.start);
-      return;
-    }
+    r.begin = take_event();
+    if (!r.begin) return;
+    (void)hipEventRecord(r.begin, stream);
   }
-  ep.cls = cls;
-  (void)hipEventRecord(ep.start, stream);
-  g_records.push_back(ep);
+  r.end = take_event();
+  if (!r.end) return;
+  g_records.push_back(r);
   idx = (long)g_records.size() - 1;
 }
 
 LaunchScope::~LaunchScope() {
-  if (idx >= 0 && idx < (long)g_records.size()) (void)hipEventRecord(g_records[idx].stop, stream);
+  if (idx < 0 || idx >= (long)g_records.size()) return;
+  (void)hipEventRecord(g_records[idx].end, stream);
+  g_chain_end = g_records[idx].end;
+  g_chain_stream = stream;
 }
 
 }  // namespace mtnlg
@@ -43,16 +65,16 @@ using namespace mtnlg;
 
 extern "C" int mtnlg_profile_enable(int on) {
   if (on) {
+    if (!g_enabled) g_chain_end = nullptr;
     g_enabled = true;
     return MTNLG_OK;
   }
   g_enabled = false;
-  for (auto &ep : g_records) g_pool.push_back(ep);
+  g_chain_end = nullptr;
   g_records.clear();
-  for (auto &ep : g_pool) {
-    (void)hipEventDestroy(ep.start);
-    (void)hipEventDestroy(ep.stop);
-  }
+  for (hipEvent_t e : g_used) g_pool.push_back(e);
+  g_used.clear();
+  for (hipEvent_t e : g_pool) (void)hipEventDestroy(e);
   g_pool.clear();
   return MTNLG_OK;
 }
@@ -64,16 +86,18 @@ extern "C" int mtnlg_profile_read(int32_t *launches, float *ms) {
     ms[i] = 0.0f;
   }
   int status = MTNLG_OK;
-  for (auto &ep : g_records) {
+  for (auto &r : g_records) {
     float t = 0.0f;
-    if (hipEventSynchronize(ep.stop) != hipSuccess || hipEventElapsedTime(&t, ep.start, ep.stop) != hipSuccess) {
+    if (hipEventSynchronize(r.end) != hipSuccess || hipEventElapsedTime(&t, r.begin, r.end) != hipSuccess) {
       status = MTNLG_HIP_ERROR;
-    } else if (ep.cls >= 0 && ep.cls < MTNLG_K_CLASSES) {
-      launches[ep.cls] += 1;
-      ms[ep.cls] += t;
+    } else if (r.cls >= 0 && r.cls < MTNLG_K_CLASSES) {
+      launches[r.cls] += 1;
+      ms[r.cls] += t;
     }
-    g_pool.push_back(ep);
   }
   g_records.clear();
+  g_chain_end = nullptr;
+  for (hipEvent_t e : g_used) g_pool.push_back(e);
+  g_used.clear();
   return status;
 }
