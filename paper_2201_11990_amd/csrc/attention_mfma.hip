@@ -184,6 +184,39 @@ __device__ __forceinline__ float quad_max(float v) {
   return fmaxf(v, __shfl_xor(v, 32, 64));
 }
 
+// Which rows (queries in the forward and dq kernels, keys in the dk/dv kernel) a wave owns.
+// Under the causal mask a 64-row block b works on b + 1 of the 64-row tiles the workgroup streams
+// (or, for keys, on all tiles from b on), so blocks taken in order would leave the workgroups of a
+// head with 1 .. s/64 tiles of work.  With eight waves the two halves of a workgroup therefore take
+// blocks p and nb - 1 - p (nb blocks in the sequence): every workgroup then computes nb + 1 wave-halves
+// of tiles, and while only one half has work in a tile it has the compute unit to itself.  With an
+// odd nb the middle block is alone in its workgroup and the other half only helps to move tiles.
+// Four waves of 32 rows (G = 2) keep consecutive 128-row blocks.
+template <int G>
+struct RowBlocks {
+  int row0;        // first row of this wave
+  int first_tile;  // lowest and highest 64-row block of the workgroup: the tile range that the
+  int last_tile;   //   forward / dq kernels (0 .. last) and the dk/dv kernel (first .. end) stream
+  bool idle;       // wave-uniform: this wave owns no rows
+  __device__ RowBlocks(int s, int pair, int wave) {
+    const int nb = (s + 63) / 64;
+    if (G == 2) {
+      row0 = pair * 128 + wave * 32;
+      first_tile = 2 * pair;
+      last_tile = 2 * pair + 1 < nb ? 2 * pair + 1 : nb - 1;
+      idle = false;
+    } else {
+      const int lo = pair, hi = nb - 1 - pair, half = wave >> 2;
+      row0 = (half ? hi : lo) * 64 + (wave & 3) * 16;
+      first_tile = lo;
+      last_tile = hi;
+      idle = half && hi == lo;
+    }
+  }
+  // workgroups along x for a sequence of s rows
+  static int grid(int s) { return G == 2 ? (s + 127) / 128 : ((s + 63) / 64 + 1) / 2; }
+};
+
 // ------------------------------------------------------------------ forward
 template <int D, int G>
 __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
@@ -191,11 +224,12 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
   constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
-  const int qt = gridDim.x - 1 - blockIdx.x, j = blockIdx.y, bi = blockIdx.z;   // long rows first
+  const int j = blockIdx.y, bi = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const int q0 = qt * 128, qw = q0 + wave * (16 * G);
+  const RowBlocks<G> rb(s, blockIdx.x, wave);
+  const int qw = rb.row0;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
@@ -224,8 +258,7 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
     l[qg] = 0.0f;
   }
 
-  const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
-  const int ntiles = last / 64 + 1;
+  const int ntiles = rb.last_tile + 1;
   // Who brings what: with four waves (G = 2) wave w brings rows 16 w .. 16 w + 15 of the K tile and of
   // the V tile; with eight (G = 1) waves 0-3 bring the K tile, waves 4-7 the V tile.
   constexpr int IPW = G * T::NI;   // DMA instructions per wave and tile
@@ -258,7 +291,7 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
     const int nn = cur == 0 ? 2 : cur - 1;   // stage of tile it + 2
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 > qw + (16 * G - 1)) {  // wave-uniform: every (query, key) pair of this wave is masked
+    if (rb.idle || kv0 > qw + (16 * G - 1)) {  // wave-uniform: every (query, key) pair of this wave is masked
       issue(it + 2, nn);
     } else {
       f32x4 sc[G][4];
@@ -365,7 +398,7 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
   for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
     const float lsum = quad_sum(l[qg]);
-    if (q < s) {
+    if (q < s && !rb.idle) {
       const float inv = 1.0f / lsum;
       bf16 *out = a + ((int64_t)bi * s + q) * ((int64_t)n * D) + (int64_t)j * D;
 #pragma unroll
@@ -389,11 +422,12 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
   constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
-  const int qt = gridDim.x - 1 - blockIdx.x, j = blockIdx.y, bi = blockIdx.z;
+  const int j = blockIdx.y, bi = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const int q0 = qt * 128, qw = q0 + wave * (16 * G);
+  const RowBlocks<G> rb(s, blockIdx.x, wave);
+  const int qw = rb.row0;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
@@ -418,7 +452,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
     }
     dsum[qg] = quad_sum(ds);
     lse2[qg] = lse[((int64_t)bi * n + j) * s + qc[qg]] * kLog2e;
-    if (q < s && g == 0) Dvec[((int64_t)bi * n + j) * s + q] = dsum[qg];
+    if (q < s && g == 0 && !rb.idle) Dvec[((int64_t)bi * n + j) * s + q] = dsum[qg];
   }
 
   f32x4 dq[G][DB];
@@ -429,8 +463,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
 #pragma unroll
       for (int e = 0; e < 4; ++e) dq[qg][db][e] = 0.0f;
 
-  const int last = q0 + 127 < s - 1 ? q0 + 127 : s - 1;
-  const int ntiles = last / 64 + 1;
+  const int ntiles = rb.last_tile + 1;
   // tile DMAs as in the forward kernel
   constexpr int IPW = G * T::NI;
   const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
@@ -469,7 +502,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
     const int nn = cur == 0 ? 2 : cur - 1;
     const char *Kt = smem + cur * STAGE, *Vt = Kt + T::BYTES;
     const int kv0 = it * 64;
-    if (kv0 > qw + (16 * G - 1)) {
+    if (rb.idle || kv0 > qw + (16 * G - 1)) {
       issue(it + 2, nn);
     } else {
       f32x4 sc[G][4], pc[G][4];
@@ -545,7 +578,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
 #pragma unroll
   for (int qg = 0; qg < G; ++qg) {
     const int q = qw + 16 * qg + lr;
-    if (q < s) {
+    if (q < s && !rb.idle) {
       bf16 *out = dqkv + ((int64_t)bi * s + q) * ld + (int64_t)j * 3 * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
@@ -567,12 +600,15 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dkv_kernel(int s, int n, flo
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
   constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES + 512;   // Q tile, dO tile, lse[64], D[64]
-  const int kt = blockIdx.x, j = blockIdx.y, bi = blockIdx.z;   // long columns first
+  const int j = blockIdx.y, bi = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
   const bf16 *dab = da + (int64_t)bi * s * pld + (int64_t)j * D;
-  const int k0 = kt * 128, kw = k0 + wave * (16 * G);
+  const RowBlocks<G> rb(s, blockIdx.x, wave);
+  // a wave without keys gets a first key beyond any sequence: every tile test below then skips it,
+  // and no register is spent on a flag (this kernel has none to spare at head size 160)
+  const int kw = rb.idle ? (1 << 30) : rb.row0;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
   const uint32_t smem_addr = lds_address(smem);
@@ -597,7 +633,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dkv_kernel(int s, int n, flo
 #pragma unroll
       for (int e = 0; e < 4; ++e) dk[kg][db][e] = dv[kg][db][e] = 0.0f;
 
-  const int t_first = k0 / 64, ntiles = (s + 63) / 64 - t_first;
+  const int t_first = rb.first_tile, ntiles = (s + 63) / 64 - t_first;
   // tile DMAs as in the forward kernel (Q tile and dO tile), plus one instruction per wave for the
   // tile's lse values (even waves) or D values (odd waves); those arrive two or four times over, so
   // that every wave issues the same number of memory operations, which the counted waits rely on
@@ -756,7 +792,7 @@ int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float
     attr = true;
   }
   LaunchScope scope(MTNLG_K_ATTN_FWD, st);
-  attn_fwd_kernel<D, FWD_G><<<dim3((s + 127) / 128, n, b), 512 / FWD_G, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a,
+  attn_fwd_kernel<D, FWD_G><<<dim3(RowBlocks<FWD_G>::grid(s), n, b), 512 / FWD_G, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a,
                                                                                     lse);
   return check_launch();
 }
@@ -776,10 +812,10 @@ int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a,
   }
   float *Dvec = (float *)ws;
   LaunchScope scope(MTNLG_K_ATTN_BWD, st);
-  attn_bwd_dq_kernel<D, DQ_G><<<dim3((s + 127) / 128, n, b), 512 / DQ_G, smem_dq, st>>>(
+  attn_bwd_dq_kernel<D, DQ_G><<<dim3(RowBlocks<DQ_G>::grid(s), n, b), 512 / DQ_G, smem_dq, st>>>(
       s, n, scale, (const bf16 *)qkv, (const bf16 *)a, lse, (const bf16 *)da, (bf16 *)dqkv, Dvec);
   MTNLG_TRY(check_launch());
-  attn_bwd_dkv_kernel<D, DKV_G><<<dim3((s + 127) / 128, n, b), 512 / DKV_G, smem_dkv, st>>>(
+  attn_bwd_dkv_kernel<D, DKV_G><<<dim3(RowBlocks<DKV_G>::grid(s), n, b), 512 / DKV_G, smem_dkv, st>>>(
       s, n, scale, (const bf16 *)qkv, lse, Dvec, (const bf16 *)da, (bf16 *)dqkv);
   return check_launch();
 }
