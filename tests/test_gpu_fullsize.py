@@ -105,8 +105,14 @@ def test_gemm_at_full_launch_shape_on_sampled_outputs(name, layout, Mm, N, K, ep
     _gemm_case(layout, Mm, N, K, epi, seed=sum(map(ord, name)))
 
 
-def test_attention_at_full_sequence_length_on_sampled_heads():
-    b, s, n, d = WL.micro_batch, WL.seq, WL.heads, WL.head_dim
+# (b, s, n, d, heads checked): the benchmark slice; the 1.3B-shaped layer (micro-batch 4, head size 128); the
+# whole unsliced layer's 128 heads; a long ragged sequence with an odd number of 64-row blocks at head size 64
+FULL_ATTENTION = [(WL.micro_batch, WL.seq, WL.heads, WL.head_dim, (0, 11)), (4, 2048, 16, 128, (5,)),
+                  (1, 2048, 128, 160, (127,)), (2, 1990, 3, 64, (2,))]
+
+
+@pytest.mark.parametrize("b,s,n,d,heads", FULL_ATTENTION, ids=[f"b{c[0]}-s{c[1]}-n{c[2]}-d{c[3]}" for c in FULL_ATTENTION])
+def test_attention_at_full_sequence_length_on_sampled_heads(b, s, n, d, heads):
     g = torch.Generator(device="cuda").manual_seed(5)
     qkv = torch.randn((b * s, 3 * n * d), generator=g, device="cuda").bfloat16()
     da = torch.randn((b * s, n * d), generator=g, device="cuda").bfloat16()
@@ -119,7 +125,7 @@ def test_attention_at_full_sequence_length_on_sampled_heads():
     M.mtnlg_attention_bwd(b, s, n, d, scale, qkv, a, lse, da, dqkv, ws)
     assert torch.isfinite(a.float()).all() and torch.isfinite(dqkv.float()).all()
     one = oracle.Dims(hidden=8, heads=1, head_dim=d, ffn=8, seq=s, batch=b)
-    for head in (0, 11):
+    for head in heads:
         q1 = to_np(qkv[:, head * 3 * d:(head + 1) * 3 * d])
         da1 = to_np(da[:, head * d:(head + 1) * d])
         assert_close(a[:, head * d:(head + 1) * d], oracle.attention_fwd(one, q1), TOL["bf16"], f"head {head} out")
