@@ -70,13 +70,13 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
     M.mtnlg_gemm(layout, A, Bm, C, bias=bias, aux=aux, epilogue=epi, workspace=ws)
     rows = sorted({r for r in (0, 1, 127, 128, 255, 256, Mm // 2 + 3, Mm - 129, Mm - 1)})
     cols = sorted({c for c in (0, 7, 255, 256, N // 2 + 5, N - 257, N - 1)})
-    An, Bn = to_np(A), to_np(Bm)
+    # operand rows / columns of the samples are picked on the device: the whole operands need not cross to the host
     if layout == B.GEMM_NT:
-        want = oracle.linear_fwd(An[rows], Bn[cols], to_np(bias)[cols] if bias is not None else None)
+        want = oracle.linear_fwd(to_np(A[rows]), to_np(Bm[cols]), to_np(bias)[cols] if bias is not None else None)
     elif layout == B.GEMM_NN:
-        want = oracle.linear_dgrad(An[rows], Bn[:, cols])
+        want = oracle.linear_dgrad(to_np(A[rows]), to_np(Bm[:, cols]))
     else:
-        want = oracle.linear_wgrad(An[:, rows], Bn[:, cols])[0]
+        want = oracle.linear_wgrad(to_np(A[:, rows]), to_np(Bm[:, cols]))[0]
     if epi & B.EPI_GELU:
         assert_close(aux[rows][:, cols], want, TOL["bf16"], "pre-activation samples")
         want = oracle.gelu(want)
@@ -97,6 +97,15 @@ FULL_GEMMS = [
     ("wfc2", B.GEMM_TN, H, F, T, 0), ("wfc1", B.GEMM_TN, F, H, T, 0), ("wproj", B.GEMM_TN, H, P, T, 0),
     ("wqkv", B.GEMM_TN, 3 * P, H, T, 0),
     ("wfc1_accumulate_fp32", B.GEMM_TN, F, H, T, B.EPI_ACCUMULATE | B.EPI_OUT_F32),
+    # the slice at micro-batch 4 (8192 tokens: four times the rows forward, four times the depth of the weight gradients)
+    ("mb4_fc1", B.GEMM_NT, 4 * T, F, H, B.EPI_BIAS | B.EPI_GELU), ("mb4_dqkv", B.GEMM_NN, 4 * T, H, 3 * P, 0),
+    ("mb4_wfc2", B.GEMM_TN, H, F, 4 * T, 0), ("mb4_wproj", B.GEMM_TN, H, P, 4 * T, 0),
+    # the whole unsliced layer (61440 QKV columns, FFN 81920: operands and outputs beyond 2^31 bytes)
+    ("full_qkv", B.GEMM_NT, T, 8 * 3 * P, H, B.EPI_BIAS), ("full_fc2", B.GEMM_NT, T, H, 8 * F, B.EPI_BIAS | B.EPI_RESIDUAL),
+    ("full_dfc2", B.GEMM_NN, T, 8 * F, H, 0), ("full_wfc1", B.GEMM_TN, 8 * F, H, T, 0),
+    # the 1.3B-shaped layer (h 2048, FFN 8192, 8192 tokens)
+    ("1p3b_qkv", B.GEMM_NT, 8192, 6144, 2048, B.EPI_BIAS), ("1p3b_dfc1", B.GEMM_NN, 8192, 2048, 8192, 0),
+    ("1p3b_wfc1", B.GEMM_TN, 8192, 2048, 8192, 0),
 ]
 
 
