@@ -1,7 +1,8 @@
 """Do the oracle's pins have teeth?  Plausible mistakes are planted in copies of the oracle's C source
 (a dropped term, a wrong sign, constant or operand, a missing scale), each copy is compiled on the CPU
 and put in the oracle's place, and the pin battery of test_oracle_pins.py has to reject every one of
-them, while the source as committed passes.  Nothing here touches the GPU library.
+them, while the source as committed passes.  The numpy references of the optimizer step and of the
+first / last stage's extras get the same treatment further down.  Nothing here touches the GPU library.
 """
 import ctypes
 import os
@@ -105,3 +106,57 @@ def test_a_planted_mistake_is_caught(name, old, new, which, tmp_path, in_place_o
     in_place_of_the_oracle(load(compile_variant(mutated, str(tmp_path), name)))
     with pytest.raises(AssertionError):
         battery()
+
+
+# ---- the numpy references of the optimizer step and of the first / last stage's extras ------------------------
+
+PY_MUTANTS = [
+    ("optimizer", "adam_without_bias_correction", "m_hat = m / (1.0 - beta1 ** step)", "m_hat = m"),
+    ("optimizer", "second_moment_of_the_gradient_itself", "v = beta2 * v + (1.0 - beta2) * g * g", "v = beta2 * v + (1.0 - beta2) * g"),
+    ("optimizer", "epsilon_under_the_root", "(np.sqrt(v_hat) + eps)", "np.sqrt(v_hat + eps)"),
+    ("optimizer", "decay_not_scaled_by_the_rate", "p = p - lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * p)",
+     "p = p - lr * (m_hat / (np.sqrt(v_hat) + eps)) - weight_decay * p"),
+    ("optimizer", "clipping_also_scales_up", "return min(1.0, max_norm / (np.sqrt(sqnorm) + 1e-6))",
+     "return max_norm / (np.sqrt(sqnorm) + 1e-6)"),
+    ("optimizer", "norm_of_absolute_values", "np.sum(np.asarray(g, dtype=np.float64) ** 2)", "np.sum(np.abs(np.asarray(g, dtype=np.float64)))"),
+    ("head", "positions_indexed_by_sequence_number", "x[t] += P[t % seq]", "x[t] += P[t // seq]"),
+    ("head", "first_row_of_a_block_skipped", "if 0 <= v < Vl:\n            x[t] = E[v]", "if 0 < v < Vl:\n            x[t] = E[v]"),
+    ("head", "maximum_not_added_back", "return np.log(s) + m - tl, m, s", "return np.log(s) - tl, m, s"),
+    ("head", "one_hot_not_subtracted", "d[t, v] -= 1.0", "d[t, v] -= 0.0"),
+    ("head", "embedding_gradient_from_the_unnormalised_input", "dE, _ = linear_wgrad(dlogits, u)", "dE, _ = linear_wgrad(dlogits, x)"),
+    ("head", "position_gradient_overwritten", "dP[t % seq] += dx[t]", "dP[t % seq] = dx[t]"),
+    ("head", "token_gradient_overwritten", "dE[v] += dx[t]", "dE[v] = dx[t]"),
+]
+PY_NAMES = {"optimizer": ("grad_sqnorm", "clip_coefficient", "adam_step"),
+            "head": ("embedding_fwd", "embedding_bwd", "cross_entropy_fwd", "cross_entropy_bwd", "lm_head_step")}
+
+
+def py_battery():
+    pins.test_adam_oracle_against_the_library_adamw_and_clip()
+    pins.test_adam_oracle_closed_forms()
+    pins.test_lm_head_oracle_against_library_autograd()
+    pins.test_vocabulary_slices_reproduce_the_unsliced_head_and_embedding()
+
+
+def module_from_text(which, text):
+    import types
+    mod = types.ModuleType(f"oracle._variant_of_{which}")
+    mod.__package__ = "oracle"
+    exec(compile(text, f"<variant of oracle/{which}.py>", "exec"), mod.__dict__)
+    return mod
+
+
+def test_the_committed_numpy_references_pass_their_battery():
+    py_battery()
+
+
+@pytest.mark.parametrize("which,name,old,new", PY_MUTANTS, ids=[m[1] for m in PY_MUTANTS])
+def test_a_mistake_planted_in_a_numpy_reference_is_caught(which, name, old, new, monkeypatch):
+    path = os.path.join(os.path.dirname(SRC), which + ".py")
+    text = open(path).read()
+    assert text.count(old) == 1, f"mutation site of {name} not found once: the source changed, update this list"
+    mod = module_from_text(which, text.replace(old, new))
+    for fn in PY_NAMES[which]:
+        monkeypatch.setattr(oracle, fn, getattr(mod, fn))
+    with pytest.raises(AssertionError):
+        py_battery()
