@@ -338,3 +338,33 @@ def test_whole_unsliced_mtnlg_layer_on_a_causal_prefix():
     assert (dx[:, n0:] == 0).all()
     for name in PARAM_NAMES:
         assert_close(grads[name], g_o.pop(name), tol, f"grad {name}")
+
+
+@pytest.mark.parametrize("count", [WL.ffn * WL.hidden, (1 << 31) + 7], ids=["fc1_slice", "beyond_2_31_elements"])
+def test_optimizer_step_at_full_tensor_sizes(count):
+    """The squared norm over the whole tensor against the oracle (converted in chunks) and one clipped Adam update
+    on sampled elements (the update is elementwise): first and last elements, the 2^31 boundary, 200000 at random."""
+    g = torch.Generator(device="cuda").manual_seed(11)
+    p = torch.randn(count, generator=g, device="cuda") * 0.004
+    m = torch.randn(count, generator=g, device="cuda") * 1e-3
+    v = torch.rand(count, generator=g, device="cuda") * 1e-6
+    grad = torch.randn(count, generator=g, device="cuda") * 0.01
+    w16 = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    near = torch.arange(-8, 8, device="cuda") + min(count - 9, 1 << 31)
+    idx = torch.cat([torch.arange(0, 1024, device="cuda"), torch.arange(count - 1031, count, device="cuda"), near,
+                     torch.randint(0, count, (200000,), generator=g, device="cuda")])
+    before = [to_np(t[idx]) for t in (p, m, v, grad)]
+    ws = torch.empty(M.mtnlg_grad_sqnorm_workspace(), dtype=torch.uint8, device="cuda")
+    sq = torch.full((1,), float("nan"), device="cuda")
+    M.mtnlg_grad_sqnorm(grad, ws, sq)
+    want_sq = sum(oracle.grad_sqnorm([to_np(c)]) for c in grad.split(1 << 26))
+    assert abs(float(sq) - want_sq) <= 1e-6 * want_sq
+    coef = oracle.clip_coefficient(want_sq, 1.0)
+    assert coef < 1.0
+    M.mtnlg_adam_step(p, m, v, grad, w16, sq, lr=1e-3, step=3, weight_decay=0.1)
+    want = oracle.adam_step(*before, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=3, clip_coef=coef)
+    for name, got, ref in zip(("weight", "m", "v"), (p, m, v), want):
+        err = np.abs(to_np(got[idx]) - ref).max()
+        assert err <= 2e-6 * np.abs(ref).max(), (name, err)
+    for lo in range(0, count, 1 << 28):   # every bf16 weight is the rounded fp32 weight
+        assert torch.equal(w16[lo:lo + (1 << 28)], p[lo:lo + (1 << 28)].to(torch.bfloat16))
