@@ -368,3 +368,33 @@ def test_optimizer_step_at_full_tensor_sizes(count):
         assert err <= 2e-6 * np.abs(ref).max(), (name, err)
     for lo in range(0, count, 1 << 28):   # every bf16 weight is the rounded fp32 weight
         assert torch.equal(w16[lo:lo + (1 << 28)], p[lo:lo + (1 << 28)].to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("b", [1, 4], ids=["micro_batch_1", "micro_batch_4"])
+def test_embedding_at_full_width(b):
+    """Token and position embedding of the first stage at h 20480, 6400 vocabulary rows of this slice (block 3 of 8),
+    sequence 2048; about one token in eight belongs to the slice, a few ids repeat many times."""
+    s, h, Vl, vs = WL.seq, WL.hidden, VOCAB_LOCAL, 3 * VOCAB_LOCAL
+    T = b * s
+    g = torch.Generator(device="cuda").manual_seed(13 + b)
+    E = (torch.randn((Vl, h), generator=g, device="cuda") * 0.02).bfloat16()
+    P = (torch.randn((s, h), generator=g, device="cuda") * 0.02).bfloat16()
+    tokens = torch.randint(0, 8 * Vl, (T,), generator=g, device="cuda", dtype=torch.int32)
+    tokens[::37] = vs + 5          # a frequent token of this slice
+    tokens[-1], tokens[0] = vs, vs + Vl - 1   # the first and the last row of the block
+    desc = B.head_desc(h, Vl, vs, s, b, "bf16")
+    x = torch.full((T, h), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_embedding_fwd(desc, tokens, E, P, x)
+    tok = tokens.cpu().numpy()
+    assert_close(x, oracle.embedding_fwd(tok, to_np(E), to_np(P), s, vs), TOL["bf16"], "embedding")
+    dx = torch.randn((T, h), generator=g, device="cuda").bfloat16()
+    dE = torch.full((Vl, h), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dP = torch.full((s, h), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_embedding_bwd(desc, tokens, dx, dE, dP)
+    dE_o, dP_o = oracle.embedding_bwd(tok, to_np(dx), Vl, s, vs)
+    assert_close(dE, dE_o, TOL["bf16"], "dE")
+    assert_close(dP, dP_o, TOL["bf16"], "dP")
+    untouched = torch.ones(Vl, dtype=torch.bool, device="cuda")
+    mine = tokens[(tokens >= vs) & (tokens < vs + Vl)].long() - vs
+    untouched[mine] = False
+    assert (dE[untouched] == 0).all(), "rows of tokens that do not occur get exactly zero gradient"
