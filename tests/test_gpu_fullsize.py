@@ -398,3 +398,30 @@ def test_embedding_at_full_width(b):
     mine = tokens[(tokens >= vs) & (tokens < vs + Vl)].long() - vs
     untouched[mine] = False
     assert (dE[untouched] == 0).all(), "rows of tokens that do not occur get exactly zero gradient"
+
+
+def test_micro_batch_loop_at_full_size_on_causal_prefixes():
+    """Two micro-batches through the 3-layer slice with fp32 gradient buffers (mtnlg_stage_step_accumulate, the
+    shape bench.py --micro-batches times): each micro-batch's y and dx and the gradients summed over both against
+    the oracle's prefix problems."""
+    wl, n0, k = WL, 12, 2
+    ws = [make_layer_params(wl, l, seed=0, device="cuda", affine="random") for l in range(wl.n_layers)]
+    acts = [_prefix_inputs(wl, n0, seed=20 + m) for m in range(k)]
+    xs, dys = torch.stack([a[0] for a in acts]), torch.stack([a[1] for a in acts])
+    run = StageRunner(wl, ws, flags=B.WGRAD_FP32)
+    ys, dxs, grads = run.step_accumulate(xs, dys)
+    torch.cuda.synchronize()
+    assert grads[0]["w_fc1"].dtype == torch.float32
+    dims = oracle_dims(wl.with_(seq=n0))
+    wn = [{name: to_np(v) for name, v in w.items()} for w in ws]
+    tol = TOL["bf16"] * 1.5  # three layers of bf16 rounding
+    total = None
+    for m in range(k):
+        y_o, dx_o, g_o = oracle.stage_step(dims, wn, _prefix_np(xs[m], n0), _prefix_np(dys[m], n0))
+        assert_close(ys[m][:, :n0], y_o, tol, f"micro-batch {m} y[:, :n0]")
+        assert_close(dxs[m][:, :n0], dx_o, tol, f"micro-batch {m} dx[:, :n0]")
+        assert (dxs[m][:, n0:] == 0).all()
+        total = g_o if total is None else [{name: a[name] + b_[name] for name in PARAM_NAMES} for a, b_ in zip(total, g_o)]
+    for l in range(wl.n_layers):
+        for name in PARAM_NAMES:
+            assert_close(grads[l][name], total[l][name], tol, f"layer {l} summed grad {name}")
