@@ -399,3 +399,39 @@ def test_embedding_lookup_and_its_gradient(dtype, b, s, h, V, vs):
     dE2 = torch.empty_like(dE)
     M.mtnlg_embedding_bwd(desc, tokens.cuda(), dx.cuda(), dE2, dP)
     assert torch.equal(dE, dE2), "fixed summation order"
+
+
+@pytest.mark.parametrize("flags", [0, B.RECOMPUTE], ids=["keep", "recompute"])
+def test_stage_step_under_graph_capture_replays_the_eager_result(flags):
+    """The step allocates nothing, never synchronises and clears nothing with memset calls, so it can be captured into
+    a HIP graph.  Replays (with other work and synchronisations between them, and with new values in the captured
+    input buffers) must give the bits of the eager step."""
+    wl = SMALL_BF16.with_(n_layers=2)
+    ws = [to_dev(make_layer_params(wl, l, seed=5, affine="random")) for l in range(wl.n_layers)]
+    run = StageRunner(wl, ws, flags=flags)
+    inputs = [tuple(t.cuda() for t in make_activations(wl, seed=30 + i)) for i in range(3)]
+    eager = []
+    for x, dy in inputs:
+        y, dx, grads = run.step(x, dy)
+        eager.append((y.clone(), dx.clone(), {k: v.clone() for k, v in grads[1].items()}))
+    x_buf, dy_buf = inputs[0][0].clone(), inputs[0][1].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # warm-up on the capture stream
+        run.step(x_buf, dy_buf)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run.step(x_buf, dy_buf)
+    for rep in range(2):
+        for (x, dy), (y_e, dx_e, g_e) in zip(inputs, eager):
+            x_buf.copy_(x)
+            dy_buf.copy_(dy)
+            run.y.fill_(float("nan"))
+            run.dx.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(run.y, y_e) and torch.equal(run.dx, dx_e), rep
+            for k in PARAM_NAMES:
+                assert torch.equal(run.grads[1][k], g_e[k]), (rep, k)
+            _ = (x.float() @ x.float().transpose(-1, -2)).sum().item()   # unrelated eager work and a sync
