@@ -184,6 +184,49 @@ def test_attention_fwd_bwd(dtype, b, s, n, d):
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", ["sharp", "rising", "falling", "constant"])
+def test_attention_with_hard_score_patterns(dtype, kind):
+    """Score rows that stress the running-maximum bookkeeping of a streamed softmax over several 64-key tiles:
+    sharp (scores of std 8: nearly one-hot rows), rising (each later key scores higher: the reference maximum
+    moves in every tile), falling (the first key dominates: everything after it underflows towards zero), constant
+    (all scores equal: the running mean of v)."""
+    b, s, n, d = 1, 330, 2, 64 if dtype == "bf16" else 16
+    g = torch.Generator().manual_seed(77)
+    q = torch.randn((s, n, d), generator=g)
+    k = torch.randn((s, n, d), generator=g)
+    v = torch.randn((s, n, d), generator=g)
+    ramp = torch.arange(s, dtype=torch.float32)[:, None, None] / 8.0
+    if kind == "sharp":
+        q, k = q * 2.8, k * 2.8
+    elif kind in ("rising", "falling"):
+        q = torch.ones((s, n, d)) + 0.1 * q
+        k = (ramp if kind == "rising" else -ramp) * torch.ones((s, n, d)) / math.sqrt(d) + 0.1 * k
+    else:
+        k = torch.zeros((s, n, d))
+    qkv = torch.stack([q, k, v], dim=2).reshape(s, 3 * n * d).to(DT[dtype])
+    da = randn((s, n * d), dtype, 78)
+    dims = oracle.Dims(hidden=8, heads=n, head_dim=d, ffn=8, seq=s, batch=b)
+    scale = 1.0 / math.sqrt(d)
+    a = torch.full((s, n * d), float("nan"), dtype=DT[dtype], device="cuda")
+    lse = torch.empty((b, n, s), device="cuda")
+    M.mtnlg_attention_fwd(b, s, n, d, scale, dev(qkv), a, lse)
+    assert torch.isfinite(lse).all()
+    assert_close(a, oracle.attention_fwd(dims, to_np(qkv)), TOL[dtype], f"{kind} attention out")
+    ws = torch.empty(M.mtnlg_attention_bwd_workspace(b, s, n, d), dtype=torch.uint8, device="cuda")
+    dqkv = torch.full(qkv.shape, float("nan"), dtype=DT[dtype], device="cuda")
+    M.mtnlg_attention_bwd(b, s, n, d, scale, dev(qkv), a, lse, dev(da), dqkv, ws)
+    want = oracle.attention_bwd(dims, to_np(qkv), to_np(da)).reshape(s, n, 3, d)
+    got = dqkv.reshape(s, n, 3, d)
+    # dv is as well conditioned as the output; dq and dk are differences of nearly equal terms when the rows are
+    # nearly one-hot, so they are held to the tolerance relative to dv's size as well
+    assert_close(got[:, :, 2], want[:, :, 2], TOL[dtype] * 1.5, f"{kind} dv")
+    ref = np.linalg.norm(want[:, :, 2])
+    for i, nm in ((0, "dq"), (1, "dk")):
+        err = np.linalg.norm(to_np(got[:, :, i]) - want[:, :, i])
+        assert err <= TOL[dtype] * 1.5 * max(np.linalg.norm(want[:, :, i]), ref), f"{kind} {nm}: {err:.3e}"
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_gelu_colsum_bias_residual(dtype):
     tol = TOL[dtype]
     z = randn((70, 264), dtype, 30, 2.0)
