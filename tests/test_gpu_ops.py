@@ -149,6 +149,41 @@ def test_layernorm_fwd_bwd(dtype, T, h):
     assert_close(dx, o_dx, tol, "ln dx without residual")
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_layernorm_rows_with_large_mean_or_no_spread(dtype):
+    """Rows whose mean is a hundred times their spread (a sum-of-squares variance would lose them in fp32), a row
+    of tiny values (eps dominates the variance) and a constant row (variance exactly 0: the output is beta)."""
+    T, h = 6, 2056
+    g = torch.Generator().manual_seed(91)
+    x = torch.randn((T, h), generator=g)
+    x[0] = 6.0 + 0.05 * x[0]
+    x[1] = -40.0 + 0.3 * x[1]
+    x[2] = 1e-4 * x[2]
+    x[3] = 3.25
+    x = x.to(DT[dtype])
+    gamma, beta = (1 + randn((h,), dtype, 92, 0.2).float()).to(DT[dtype]), randn((h,), dtype, 93, 0.2)
+    out = torch.empty((T, h), dtype=DT[dtype], device="cuda")
+    mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
+    M.mtnlg_layernorm_fwd(dev(x), dev(gamma), dev(beta), 1e-5, out, mean, rstd)
+    o_out, o_mean, o_rstd = oracle.layernorm_fwd(to_np(x), to_np(gamma), to_np(beta), 1e-5)
+    for t in range(T):
+        assert_close(out[t], o_out[t], TOL[dtype], f"row {t} out")
+    assert np.abs(to_np(rstd) / o_rstd - 1).max() <= 2e-5
+    assert torch.equal(out[3].cpu(), beta.to(DT[dtype])), "a constant row normalises to beta exactly"
+    dout = randn((T, h), dtype, 94)
+    ws = torch.empty(M.mtnlg_layernorm_bwd_workspace(T, h), dtype=torch.uint8, device="cuda")
+    dx = torch.empty_like(out)
+    dgamma, dbeta = (torch.full((h,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2))
+    M.mtnlg_layernorm_bwd(dev(x), dev(gamma), mean, rstd, dev(dout), dx, dgamma, dbeta, ws, grad_f32=True)
+    o_dx, o_dg, o_db = oracle.layernorm_bwd(to_np(x), to_np(gamma), o_mean, o_rstd, to_np(dout))
+    # backward runs on the GPU's own fp32 statistics: the mean of the row around -40 carries ~2e-6 of absolute
+    # rounding error against a spread of 0.3, i.e. ~1e-5 in xhat, hence three times the fp32 bar
+    for t in range(T):
+        assert_close(dx[t], o_dx[t], TOL[dtype] * (1 if dtype == "bf16" else 3), f"row {t} dx")
+    assert_close(dgamma, o_dg, TOL[dtype] * (1 if dtype == "bf16" else 3), "dgamma")
+    assert_close(dbeta, o_db, TOL[dtype], "dbeta")
+
+
 ATT_CASES = [(2, 40, 3, 64), (1, 130, 2, 128), (2, 77, 2, 160), (1, 1, 1, 8), (1, 300, 1, 32), (1, 257, 2, 160),
              (1, 700, 2, 160), (1, 520, 1, 64), (2, 390, 1, 128)]   # many streamed tiles: the three-stage ring wraps
 
