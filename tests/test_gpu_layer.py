@@ -334,6 +334,23 @@ def test_lm_head_step_against_the_oracle(dtype, b, s, h, V):
             assert_close(gt, wt, tol, f"lm head {name}")
 
 
+def test_cross_entropy_with_logits_far_from_zero():
+    """Logits of several hundred in magnitude (an embedding forty times larger than usual): exponentials taken
+    without the row maximum would overflow.  fp32 path; the loss is compared relatively (it is large here)."""
+    b, s, h, V = 2, 20, 136, 300
+    T = b * s
+    x, gamma, beta, E, targets, dloss = _head_inputs("fp32", T, h, V, seed=5)
+    E = E * 40.0
+    want = oracle.lm_head_step(to_np(x), to_np(gamma), to_np(beta), to_np(E), to_np(targets), to_np(dloss))
+    logits = oracle.linear_fwd(oracle.layernorm_fwd(to_np(x), to_np(gamma), to_np(beta), 1e-5)[0], to_np(E))
+    assert np.abs(logits).max() > 100.0
+    got = _run_head(B.head_desc(h, V, 0, s, b, "fp32"), x, gamma, beta, E, targets, dloss)
+    assert torch.isfinite(got[0]).all()
+    assert np.abs(to_np(got[0]) - want[0]).max() <= 1e-5 * np.abs(want[0]).max()
+    for name, gt, wt in zip(("dx", "dgamma", "dbeta", "dE"), got[1:], want[1:]):
+        assert_close(gt, wt, 3e-5, f"lm head {name}")
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_vocabulary_sliced_head_exchanges_one_maximum_and_three_sums(dtype):
     """Two ranks with half of E's rows each; the hook hands every rank the group's value at the four exchange
