@@ -89,3 +89,38 @@ def test_null_pointers_and_small_workspace_are_reported_before_any_gpu_work():
     assert L.mtnlg_layernorm_fwd(1, 4, 12, one, None, None, one, one, 1e-5, None, one, one, one, None) == -3
     assert L.mtnlg_attention_fwd(1, 1, 8, 1, 8, 0.0, one, one, one, None) == -1
     assert L.mtnlg_colsum(1, 4, 12, one, one, 0, 0, one, None) == -3
+
+
+def test_empty_problems_are_rejected_before_any_gpu_work():
+    """A size of zero anywhere is an argument error (MTNLG_INVALID_ARG), never a launch; size queries answer 0."""
+    L = B.lib()
+    one, two = ctypes.c_void_p(256), ctypes.c_void_p(512)
+    f = ctypes.c_float
+    i64 = ctypes.c_int64
+    for M_, N_, K_ in ((0, 8, 8), (8, 0, 8), (8, 8, 0)):
+        assert L.mtnlg_gemm(1, 0, i64(M_), i64(N_), i64(K_), one, one, two, None, None, 0, None, 0, None) == -1
+    assert L.mtnlg_layernorm_fwd(1, i64(0), i64(16), one, None, None, one, one, f(1e-5), None, two, one, one, None) == -1
+    assert L.mtnlg_layernorm_bwd(1, i64(0), i64(16), one, one, one, one, one, None, two, one, one, None, 1, 0, one, None) == -1
+    assert L.mtnlg_attention_fwd(1, 1, 0, 1, 64, f(0.125), one, two, one, None) == -1
+    assert L.mtnlg_attention_bwd(1, 0, 8, 1, 64, f(0.125), one, one, one, one, two, one, None) == -1
+    assert L.mtnlg_attention_bwd_workspace(1, 0, 1, 64) == 0
+    assert L.mtnlg_gelu_fwd(1, 0, i64(0), one, two, None) == -1
+    assert L.mtnlg_gelu_bwd(1, 0, i64(0), one, one, two, None) == -1
+    assert L.mtnlg_colsum(1, i64(0), i64(16), one, two, 0, 0, one, None) == -1
+    assert L.mtnlg_bias_residual(1, i64(0), i64(16), one, one, None, two, None) == -1
+    assert L.mtnlg_grad_sqnorm(i64(0), one, one, one, 0, None) == -1
+    adam = B.AdamDesc(1e-3, 0.9, 0.95, 1e-8, 0.1, 1.0, 1)
+    assert L.mtnlg_adam_step(ctypes.byref(adam), i64(0), one, one, one, one, None, None, None) == -1
+    d = B.desc_from_workload(WORKLOADS["tiny_fp32"])
+    tbl = B._Ptrs12(*([256] * 12))
+    nohook = ctypes.cast(None, B.REDUCE_FN)
+    assert L.mtnlg_stage_step_accumulate(ctypes.byref(d), 1, ctypes.byref(tbl), 0, one, one, two, two, ctypes.byref(tbl),
+                                         one, 1 << 40, one, 1 << 40, nohook, None, None) == -1
+    for field in ("seq", "micro_batch", "hidden", "heads_local", "ffn_local"):
+        bad = B.desc_from_workload(WORKLOADS["tiny_fp32"])
+        setattr(bad, field, 0)
+        assert L.mtnlg_layer_desc_check(ctypes.byref(bad)) == -1, field
+        assert L.mtnlg_saved_bytes(ctypes.byref(bad)) == 0 and L.mtnlg_workspace_bytes(ctypes.byref(bad)) == 0
+    head = B.head_desc(64, 0, 0, 8, 1, "fp32")
+    assert L.mtnlg_lm_head_workspace(ctypes.byref(head)) == 0
+    assert L.mtnlg_embedding_fwd(ctypes.byref(head), one, one, one, two, ctypes.cast(None, B.REDUCE_OP_FN), None, None) == -1
