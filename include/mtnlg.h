@@ -57,14 +57,20 @@
 extern "C" {
 #endif
 
+/* Every int-returning entry point returns one of these.  Arguments are checked before any
+ * launch: a size or count <= 0 (an empty problem), an unknown enum value, a non-finite scale or
+ * aliasing the call forbids is MTNLG_INVALID_ARG; a missing required pointer MTNLG_NULL_POINTER;
+ * a shape the kernels do not cover (e.g. widths that are not multiples of 8 on the bf16 path)
+ * MTNLG_UNSUPPORTED_SHAPE; after an error the outputs are unspecified.  Size queries return 0
+ * for descriptors that would be rejected. */
 enum mtnlg_status {
   MTNLG_OK = 0,
   MTNLG_INVALID_ARG = -1,
   MTNLG_NULL_POINTER = -2,
   MTNLG_UNSUPPORTED_SHAPE = -3,
   MTNLG_WORKSPACE_TOO_SMALL = -4,
-  MTNLG_HIP_ERROR = -5,
-  MTNLG_REDUCE_FAILED = -6
+  MTNLG_HIP_ERROR = -5,      /* a launch was refused (hipGetLastError after it; no synchronisation) */
+  MTNLG_REDUCE_FAILED = -6   /* the caller's reduce hook returned non-zero */
 };
 
 enum mtnlg_dtype { MTNLG_F32 = 0, MTNLG_BF16 = 1 };
