@@ -16,8 +16,9 @@
 //        block with 16-byte loads along the row axis, transposes it in registers and writes
 //        16-byte k-runs.
 //    Inside a tile, the 16-byte chunk c of row r sits at chunk position
-//    c ^ (r & 7) ^ ((r >> 3) & 7), which keeps both kinds of LDS writes and the MFMA operand
-//    reads free of bank conflicts.  Workgroup = WGM x WGN waves (256x256 tile on 2 x 4 waves by
+//    c ^ (r & 7) ^ ((r >> 3) & 7), chosen from a bank model (an LDS pass serving 16 consecutive
+//    lanes) for both kinds of LDS writes and the 32-row MFMA operand reads; unlike the streaming
+//    kernel's placement it has not been measured.  Workgroup = WGM x WGN waves (256x256 tile on 2 x 4 waves by
 //    default, 128x128 on 2 x 2 for small problems); K advances 64 at a time through two LDS
 //    stages, with the LDS traffic interleaved between the MFMAs by scheduling hints.
 //    Requirements: K % 8 == 0 and N % 8 == 0; a row-contiguous A also needs M % 8 == 0 (16-byte
