@@ -20,6 +20,42 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0     # MI355X HBM3E
+
+
+def measured_peaks(x, reps=5):
+    """What the chip sustains in this process, on this data, before the timed steps: (a) a loop of nothing but bf16
+    matrix-core instructions (mtnlg_calibrate_mfma) on operands drawn like the workload's activations, long enough
+    (about 20 ms a launch) for the clock to settle under the power limit; (b) a plain streaming copy of 1 GiB
+    (mtnlg_calibrate_copy).  Both are timed with events on the launch stream."""
+    import torch
+
+    import paper_2201_11990_amd as M
+
+    wgs, iters = 256 * 4, 6000
+    n = M.mtnlg_calibrate_mfma_operand_bytes(wgs) // 2
+    ops = x.reshape(-1)
+    ops = ops[:n].contiguous() if ops.numel() >= n else torch.randn(n, device=x.device).bfloat16()
+    out = torch.empty(wgs * 512, device=x.device)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=x.device).fill_(1)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_mfma = timed(lambda: M.mtnlg_calibrate_mfma(wgs, iters, ops, out))
+    ms_copy = timed(lambda: M.mtnlg_calibrate_copy(dst, src))
+    fl = M.mtnlg_calibrate_mfma_flops(wgs, iters)
+    return {"mfma_tflops": fl / (ms_mfma * 1e-3) / 1e12, "mfma_ms": ms_mfma,
+            "copy_gbps": 2 * (1 << 30) / (ms_copy * 1e-3) / 1e9, "copy_ms": ms_copy}
 
 
 def gemm_flops_per_step(wl):
@@ -169,6 +205,8 @@ def main():
     ap.add_argument("--optimizer-step", action="store_true",
                     help="also time the Adam step (squared gradient norm + fused update) over all parameters of the "
                          "stage and add an `optimizer_step` object (HBM roofline) to the line")
+    ap.add_argument("--no-measured-peak", action="store_true",
+                    help="skip the matrix-core-only loop and the 1 GiB copy that measure what the chip sustains")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
     args = ap.parse_args()
@@ -208,6 +246,10 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    peaks = None if args.no_measured_peak else measured_peaks(x)
+    if peaks is not None:   # the probe leaves the chip hot and clocked down: let one untimed step pass
+        one_step()
+        torch.cuda.synchronize()
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -265,9 +307,26 @@ def main():
         traffic = counter_traffic(dom) if wl.name == "mtnlg_tp8_stage" and args.micro_batches == 1 else None
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                           "traffic_source": "profiles/stage_step_mtnlg_tp8_hbm_traffic.txt (two rocprofv3 --pmc runs "
+                                             "of this command; counters cannot be read inside the timed run)",
                            "all_gemm_tflops": round(sum(gf.values()) / (g_ms * 1e-3) / 1e12, 1),
                            "gemm_share_of_step": round(g_ms / ms, 3)}
+        if peaks is not None:
+            # the same fractions against what a loop of nothing but matrix-core instructions sustains here
+            out["roofline"]["measured_peak"] = round(peaks["mfma_tflops"], 1)
+            out["roofline"]["frac_of_measured"] = round(ach / peaks["mfma_tflops"], 4)
+            out["pct_of_measured_mfma_loop"] = round(100 * value / peaks["mfma_tflops"], 2)
+        # bandwidth-bound classes: achieved GB/s on their algorithmic bytes against the HBM peak
+        per_launch = flops.hbm_bytes_per_launch(wl)
+        for k, nbytes in per_launch.items():
+            if k in classes and prof[k][1] > 0:
+                gbps = prof[k][0] * nbytes / (prof[k][1] * 1e-3) / 1e9
+                classes[k].update({"bound": "hbm", "bytes_per_launch": int(nbytes), "gbps": round(gbps, 1),
+                                   "frac_hbm": round(gbps / PEAK_HBM_GBPS, 4)})
         out["kernel_classes"] = classes
+        if peaks is not None:
+            out["hbm_copy_1gib"] = {"ms": round(peaks["copy_ms"], 4), "gbps": round(peaks["copy_gbps"], 1),
+                                    "frac_hbm": round(peaks["copy_gbps"] / PEAK_HBM_GBPS, 4)}
     else:
         out["roofline"] = {"bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": None, "traffic": None}

@@ -30,8 +30,9 @@
  *
  * ALL data pointers are DEVICE pointers (HIP global memory) unless stated.
  * Descriptor / weight-table / grad-table structs themselves live in HOST memory.
- * The library allocates no device memory, keeps no global state, launches only
- * on the stream it is given and never synchronises the host.
+ * The library allocates no device memory, launches only on the stream it is
+ * given and never synchronises the host.  Its only process-wide state: per-device
+ * marks that a kernel's attributes have been set and the optional timing record.
  *
  * Layouts (row-major everywhere):
  *   activations  [micro_batch, seq, hidden], hidden contiguous
@@ -351,6 +352,21 @@ enum mtnlg_kernel_class {
 };
 int mtnlg_profile_enable(int on);
 int mtnlg_profile_read(int32_t *launches /*[MTNLG_K_CLASSES]*/, float *ms /*[MTNLG_K_CLASSES]*/);
+
+/* --- measurement aids: what the chip sustains, with the benchmark's data, on the two resources that
+ *     bound the layer's kernels (the throughput figures of the paper's Section 2.4 are fractions of a peak;
+ *     these give the peak as measured next to the nominal one) ----------------------------------------------
+ * mtnlg_calibrate_mfma: `workgroups` workgroups of 8 waves run `iters` rounds of 8 bf16 matrix-core
+ * instructions (16x16x32, fp32 accumulate) each on fragments taken from `operands` (device, bf16,
+ * mtnlg_calibrate_mfma_operand_bytes(workgroups) bytes, any finite values: the clock the power limit allows
+ * depends on the data); nothing else runs in the loop.  out: device float[workgroups * 512], written.  The
+ * work is mtnlg_calibrate_mfma_flops(workgroups, iters) FLOP; the caller times the launch.
+ * mtnlg_calibrate_copy: dst[0..bytes) = src[0..bytes) (device, 16-byte aligned, bytes a multiple of 16, no
+ * overlap) by a plain streaming kernel: 2 * bytes of HBM traffic. */
+size_t mtnlg_calibrate_mfma_operand_bytes(int workgroups);
+int64_t mtnlg_calibrate_mfma_flops(int workgroups, int iters);
+int mtnlg_calibrate_mfma(int workgroups, int iters, const void *operands, float *out, void *stream);
+int mtnlg_calibrate_copy(void *dst, const void *src, int64_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -118,6 +118,10 @@ def lib():
             "mtnlg_colsum_workspace": (sz, [i64, i64]),
             "mtnlg_colsum": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp]),
             "mtnlg_bias_residual": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]),
+            "mtnlg_calibrate_mfma_operand_bytes": (sz, [ctypes.c_int]),
+            "mtnlg_calibrate_mfma_flops": (i64, [ctypes.c_int, ctypes.c_int]),
+            "mtnlg_calibrate_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, vp, vp]),
+            "mtnlg_calibrate_copy": (ctypes.c_int, [vp, vp, i64, vp]),
             "mtnlg_profile_enable": (ctypes.c_int, [ctypes.c_int]),
             "mtnlg_profile_read": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]),
         }
@@ -135,8 +139,8 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
             "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
             "mtnlg_lm_head_workspace", "mtnlg_embedding_fwd", "mtnlg_embedding_bwd", "mtnlg_lm_head_step",
-            "mtnlg_profile_enable",
-            "mtnlg_profile_read")
+            "mtnlg_calibrate_mfma_operand_bytes", "mtnlg_calibrate_mfma_flops", "mtnlg_calibrate_mfma",
+            "mtnlg_calibrate_copy", "mtnlg_profile_enable", "mtnlg_profile_read")
 
 
 def status_string(status):
@@ -384,16 +388,6 @@ def _op_hook(reduce):
     return REDUCE_OP_FN(cb)
 
 
-def _copy_into_pointer(ptr, src):
-    """Copy a contiguous device tensor over the device memory at `ptr` (for exchange hooks)."""
-    hip = ctypes.CDLL("libamdhip64.so")
-    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
-    rc = hip.hipMemcpyAsync(ctypes.c_void_p(ptr), ctypes.c_void_p(src.data_ptr()), _nbytes(src), 3, _stream())
-    if rc != 0:
-        raise RuntimeError(f"hipMemcpyAsync failed: {rc}")
-    torch.cuda.current_stream().synchronize()   # src may be freed by the caller right after
-
-
 def mtnlg_lm_head_workspace(desc):
     return lib().mtnlg_lm_head_workspace(ctypes.byref(desc))
 
@@ -439,6 +433,25 @@ def mtnlg_adam_step(master, m, v, grad, weight_bf16=None, sqnorm=None, *, lr, st
     d = AdamDesc(lr, beta1, beta2, eps, weight_decay, max_grad_norm, step)
     _check(lib().mtnlg_adam_step(ctypes.byref(d), master.numel(), _p(master), _p(m), _p(v), _p(grad), _p(weight_bf16),
                                  _p(sqnorm), _stream()), "mtnlg_adam_step")
+
+
+def mtnlg_calibrate_mfma_operand_bytes(workgroups):
+    return lib().mtnlg_calibrate_mfma_operand_bytes(workgroups)
+
+
+def mtnlg_calibrate_mfma_flops(workgroups, iters):
+    return lib().mtnlg_calibrate_mfma_flops(workgroups, iters)
+
+
+def mtnlg_calibrate_mfma(workgroups, iters, operands, out):
+    assert operands.dtype == torch.bfloat16 and _nbytes(operands) >= mtnlg_calibrate_mfma_operand_bytes(workgroups)
+    assert out.dtype == torch.float32 and out.numel() >= workgroups * 512
+    _check(lib().mtnlg_calibrate_mfma(workgroups, iters, _p(operands), _p(out), _stream()), "mtnlg_calibrate_mfma")
+
+
+def mtnlg_calibrate_copy(dst, src):
+    assert _nbytes(dst) == _nbytes(src)
+    _check(lib().mtnlg_calibrate_copy(_p(dst), _p(src), _nbytes(src), _stream()), "mtnlg_calibrate_copy")
 
 
 def mtnlg_profile_enable(on):

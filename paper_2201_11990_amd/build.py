@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmtnlg.so")
 OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ("api.cpp", "profile.cpp", "elementwise.hip", "gemm_generic.hip", "gemm_mfma.hip",
-           "attention_simple.hip", "attention_mfma.hip", "optimizer.hip", "head.hip")
+           "attention_simple.hip", "attention_mfma.hip", "optimizer.hip", "head.hip", "calibrate.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]

@@ -34,7 +34,11 @@ int make_shape(const mtnlg_layer_desc *D, Shape *S) {
   if ((int64_t)D->seq * D->micro_batch > (int64_t)1 << 30) return MTNLG_UNSUPPORTED_SHAPE;
   if ((int64_t)D->heads_local * D->head_dim > (int64_t)1 << 24 || D->ffn_local > 1 << 24)
     return MTNLG_UNSUPPORTED_SHAPE;
-  if (D->seq > 4096 && !attention_mfma_supported(D->dtype, D->head_dim)) return MTNLG_UNSUPPORTED_SHAPE;
+  // attention: the MFMA kernels within their limits, otherwise the vector-ALU kernels up to their sequence limit,
+  // decided here so that a layer call fails before its first launch
+  if (!attention_mfma_takes(D->dtype, D->micro_batch, D->seq, D->heads_local, D->head_dim) &&
+      (D->seq > ATTENTION_SIMPLE_MAX_SEQ || D->heads_local > 65535 || D->micro_batch > 65535))
+    return MTNLG_UNSUPPORTED_SHAPE;
   S->b = D->micro_batch; S->s = D->seq; S->n = D->heads_local; S->d = D->head_dim;
   S->T = (int64_t)S->b * S->s; S->h = D->hidden; S->p = (int64_t)S->n * S->d; S->F = D->ffn_local;
   S->dtype = D->dtype;
@@ -388,7 +392,7 @@ int mtnlg_attention_fwd(int dtype, int32_t b, int32_t s, int32_t n, int32_t d, f
                         void *a, float *lse, void *stream) {
   if (!qkv || !a || !lse) return MTNLG_NULL_POINTER;
   if (b <= 0 || s <= 0 || n <= 0 || d <= 0 || !(scale > 0.0f)) return MTNLG_INVALID_ARG;
-  if (attention_mfma_supported(dtype, d))
+  if (attention_mfma_takes(dtype, b, s, n, d))
     return attention_fwd_mfma(b, s, n, d, scale, qkv, a, lse, (hipStream_t)stream);
   return attention_fwd_simple(dtype, b, s, n, d, scale, qkv, a, lse, (hipStream_t)stream);
 }
@@ -403,7 +407,7 @@ int mtnlg_attention_bwd(int dtype, int32_t b, int32_t s, int32_t n, int32_t d, f
                         void *stream) {
   if (!qkv || !a || !lse || !da || !dqkv || !workspace) return MTNLG_NULL_POINTER;
   if (b <= 0 || s <= 0 || n <= 0 || d <= 0 || !(scale > 0.0f)) return MTNLG_INVALID_ARG;
-  if (attention_mfma_supported(dtype, d))
+  if (attention_mfma_takes(dtype, b, s, n, d))
     return attention_bwd_mfma(b, s, n, d, scale, qkv, a, lse, da, dqkv, workspace, (hipStream_t)stream);
   return attention_bwd_simple(dtype, b, s, n, d, scale, qkv, a, lse, da, dqkv, workspace, (hipStream_t)stream);
 }

@@ -784,12 +784,13 @@ constexpr int FWD_G = 1, DQ_G = 1, DKV_G = 1;
 template <int D>
 int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
   constexpr int smem = 3 * 2 * 64 * D * 2;
-  static bool attr = false;
-  if (!attr) {
+  static unsigned long long attr_done = 0;
+  int device;
+  if (!attr_is_set(attr_done, &device)) {
     if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D, FWD_G>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
         hipSuccess)
       return MTNLG_HIP_ERROR;
-    attr = true;
+    attr_mark_set(attr_done, device);
   }
   LaunchScope scope(MTNLG_K_ATTN_FWD, st);
   attn_fwd_kernel<D, FWD_G><<<dim3(RowBlocks<FWD_G>::grid(s), n, b), 512 / FWD_G, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a,
@@ -801,14 +802,15 @@ template <int D>
 int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a, const float *lse, const void *da,
                void *dqkv, void *ws, hipStream_t st) {
   constexpr int smem_dq = 3 * 2 * 64 * D * 2, smem_dkv = 3 * (2 * 64 * D * 2 + 512);
-  static bool attr = false;
-  if (!attr) {
+  static unsigned long long attr_done = 0;
+  int device;
+  if (!attr_is_set(attr_done, &device)) {
     if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D, DQ_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             smem_dq) != hipSuccess ||
         hipFuncSetAttribute((const void *)attn_bwd_dkv_kernel<D, DKV_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             smem_dkv) != hipSuccess)
       return MTNLG_HIP_ERROR;
-    attr = true;
+    attr_mark_set(attr_done, device);
   }
   float *Dvec = (float *)ws;
   LaunchScope scope(MTNLG_K_ATTN_BWD, st);
@@ -826,6 +828,10 @@ bool fits(int s, int n, int d) { return (int64_t)s * n * 3 * d * 2 < ((int64_t)1
 }  // namespace
 
 bool attention_mfma_supported(int dtype, int d) { return dtype == MTNLG_BF16 && (d == 64 || d == 128 || d == 160); }
+
+bool attention_mfma_takes(int dtype, int b, int s, int n, int d) {
+  return attention_mfma_supported(dtype, d) && n <= 65535 && b <= 65535 && fits(s, n, d);
+}
 
 size_t attention_bwd_workspace_bytes(int b, int s, int n, int) { return (size_t)b * n * s * sizeof(float); }
 

@@ -13,7 +13,7 @@
 namespace mtnlg {
 
 constexpr int ATT_MAX_D = 256;
-constexpr int ATT_SIMPLE_MAX_S = 4096;
+constexpr int ATT_SIMPLE_MAX_S = ATTENTION_SIMPLE_MAX_SEQ;
 
 template <typename E>
 __device__ __forceinline__ float dot_row(const float *__restrict__ a_lds, const E *__restrict__ row, int d) {

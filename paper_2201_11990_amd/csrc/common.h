@@ -67,7 +67,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // read it cannot tell apart from it wait for all outstanding memory operations, which empties a
 // ring of several stages at every tile.  Kernels that use these count their outstanding DMAs
 // themselves (s_waitcnt vmcnt(N) before the barrier that publishes a stage).  The LDS address
-// travels in M0, which no other instruction of those kernels reads.
+// travels in M0, which each statement declares as clobbered.
 typedef __attribute__((ext_vector_type(4))) int dma_rsrc_t;
 __device__ __forceinline__ dma_rsrc_t dma_rsrc(const void *base) {   // base: the same in every lane
   const uint64_t a = (uint64_t)base;
@@ -78,6 +78,10 @@ __device__ __forceinline__ dma_rsrc_t dma_rsrc(const void *base) {   // base: th
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
+// The compiler keeps M0 out of register allocation ("reserved") and warns about it in a clobber list; the
+// clobber is still what tells it that its own M0 initialisations do not survive these statements.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 // TAG only tells call sites apart: the compiler merges identical asm statements on the two sides
 // of a branch into one burst in front of it, which is exactly what spreading them tries to avoid.
 template <int TAG = 0>
@@ -85,15 +89,17 @@ __device__ __forceinline__ void dma16(dma_rsrc_t rs, uint32_t lds_dst, uint32_t 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds ; site %3" ::"s"(
                    __builtin_amdgcn_readfirstlane(lds_dst)),
                "v"(byte_offset), "s"(rs), "n"(TAG)
-               : "memory");
+               : "memory", "m0");
 }
 template <int TAG = 0>
 __device__ __forceinline__ void dma4(dma_rsrc_t rs, uint32_t lds_dst, uint32_t byte_offset) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds ; site %3" ::"s"(
                    __builtin_amdgcn_readfirstlane(lds_dst)),
                "v"(byte_offset), "s"(rs), "n"(TAG)
-               : "memory");
+               : "memory", "m0");
 }
+
+#pragma clang diagnostic pop
 
 // GeLU in fp32.  tanh form: 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))); erf form:
 // 0.5 z (1 + erf(z / sqrt 2)).
@@ -152,6 +158,18 @@ struct LaunchScope {
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? MTNLG_OK : MTNLG_HIP_ERROR; }
 
+// Kernel attributes (dynamic LDS size) are set once per device and kernel: `done` is a bit mask of
+// the devices on which the attribute of one kernel has been set (devices beyond 63 set it every time).
+// Thread-safe; a race sets the attribute twice, which is harmless.
+inline bool attr_is_set(unsigned long long &done, int *device) {
+  if (hipGetDevice(device) != hipSuccess) { *device = -1; return false; }
+  if (*device < 0 || *device > 63) return false;
+  return (__atomic_load_n(&done, __ATOMIC_ACQUIRE) >> *device) & 1ull;
+}
+inline void attr_mark_set(unsigned long long &done, int device) {
+  if (device >= 0 && device <= 63) __atomic_fetch_or(&done, 1ull << device, __ATOMIC_RELEASE);
+}
+
 #define MTNLG_TRY(expr)            \
   do {                             \
     int st__ = (expr);             \
@@ -181,6 +199,9 @@ int attention_bwd_simple(int dtype, int b, int s, int n, int d, float scale, con
 
 // MFMA attention (bf16): which head sizes it takes, its scratch need, its launchers
 bool attention_mfma_supported(int dtype, int d);
+// ... and whether it takes this problem (grid limits, 32-bit byte offsets inside one sequence)
+bool attention_mfma_takes(int dtype, int b, int s, int n, int d);
+constexpr int ATTENTION_SIMPLE_MAX_SEQ = 4096;   // the vector-ALU kernels hold one row of scores in LDS
 size_t attention_bwd_workspace_bytes(int b, int s, int n, int d);
 int attention_fwd_mfma(int b, int s, int n, int d, float scale, const void *qkv, void *a, float *lse,
                        hipStream_t stream);

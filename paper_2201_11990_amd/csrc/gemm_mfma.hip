@@ -26,8 +26,6 @@
 //
 // Workgroups are numbered so that the 8 XCDs (workgroup id mod 8) each own a contiguous run of
 // column-major tiles: neighbours in an XCD's L2 share A and B panels.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace mtnlg {
@@ -754,25 +752,26 @@ int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
   const unsigned grid = (unsigned)(g.per_xcd * 8 + (split ? plan.tail * plan.split : 0));
   constexpr int stages = 2 * (BM + BN) * BK * 2, image = (BM / WGM) * BN * 4;
   constexpr int smem = stages > image ? stages : image;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static unsigned long long attr_done = 0;
+  int device;
+  if (!attr_is_set(attr_done, &device)) {
     if (hipFuncSetAttribute((const void *)gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return MTNLG_HIP_ERROR;
-    attr_set = true;
+    attr_mark_set(attr_done, device);
   }
   // Aligned problems on the default tile shape take the streaming kernel (all operands by DMA).
   if constexpr (BM == 256 && BN == 256 && WGM == 2 && WGN == 4 && !KTAIL) {
     if (g.M % 256 == 0 && g.N % 256 == 0) {
       constexpr int stream_smem = 5 * 256 * BK * 2;
-      static bool stream_attr_set = false;
-      if (!stream_attr_set) {
+      static unsigned long long stream_attr_done = 0;
+      if (!attr_is_set(stream_attr_done, &device)) {
         if (hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess)
           return MTNLG_HIP_ERROR;
-        stream_attr_set = true;
+        attr_mark_set(stream_attr_done, device);
       }
       // bf16 output with nothing but an optional bias: the epilogue that rounds before it transposes
       if ((g.ea.flags & ~(uint32_t)MTNLG_EPI_BIAS) == 0)
@@ -819,12 +818,6 @@ int launch_config(int cfg, const GemmArgs &g, void *ws, size_t ws_bytes, hipStre
 
 template <bool AT, bool BT>
 int pick_tile(const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
-  // MTNLG_GEMM_TILE=<0..4> forces one tile shape (tuning aid).
-  static const int forced = [] {
-    const char *e = getenv("MTNLG_GEMM_TILE");
-    return e ? atoi(e) : -1;
-  }();
-  if (forced >= 0 && forced < TILE_CONFIGS) return launch_config<AT, BT>(forced, g, ws, ws_bytes, st);
   // 256x256 tiles on 8 waves measure fastest per tile.  A last round that would leave
   // most CUs idle is split along K instead (needs workspace); without workspace, problems
   // too small to give most CUs one big tile take 128x128 tiles (two workgroups per CU).

@@ -190,6 +190,7 @@ int head_desc_check(const mtnlg_head_desc *d) {
   if (!d) return MTNLG_NULL_POINTER;
   if (d->dtype != MTNLG_F32 && d->dtype != MTNLG_BF16) return MTNLG_INVALID_ARG;
   if (d->hidden <= 0 || d->vocab_local <= 0 || d->vocab_start < 0 || d->seq <= 0 || d->micro_batch <= 0) return MTNLG_INVALID_ARG;
+  if (!(d->ln_eps >= 0.0f) || !isfinite(d->ln_eps)) return MTNLG_INVALID_ARG;
   if (d->hidden % 8 != 0) return MTNLG_UNSUPPORTED_SHAPE;   // 16-byte row accesses
   if (d->dtype == MTNLG_BF16 && d->vocab_local % 8 != 0) return MTNLG_UNSUPPORTED_SHAPE;
   return MTNLG_OK;
@@ -199,7 +200,7 @@ inline char *at(void *base, size_t off) { return static_cast<char *>(base) + off
 
 int call_hook(mtnlg_reduce_op_fn reduce, void *user, void *buf, size_t count, int dtype, int op, hipStream_t st) {
   if (!reduce) return MTNLG_OK;
-  return reduce(buf, count, dtype, op, (void *)st, user) == 0 ? MTNLG_OK : MTNLG_INVALID_ARG;
+  return reduce(buf, count, dtype, op, (void *)st, user) == 0 ? MTNLG_OK : MTNLG_REDUCE_FAILED;
 }
 
 }  // namespace
@@ -270,6 +271,7 @@ int mtnlg_lm_head_step(const mtnlg_head_desc *desc, const void *x, const void *l
   head_layout(desc, &W);
   if (workspace_bytes < W.total) return MTNLG_WORKSPACE_TOO_SMALL;
   const int dt = desc->dtype;
+  const float eps = desc->ln_eps > 0.0f ? desc->ln_eps : 1e-5f;   // 0 = the default, as in the layer descriptor
   const int64_t T = (int64_t)desc->micro_batch * desc->seq, h = desc->hidden, Vl = desc->vocab_local;
   hipStream_t st = (hipStream_t)stream;
   void *u = at(workspace, W.u), *dlogits = at(workspace, W.dlogits), *du = at(workspace, W.du);
@@ -279,7 +281,7 @@ int mtnlg_lm_head_step(const mtnlg_head_desc *desc, const void *x, const void *l
   void *gws = at(workspace, W.gemm);
 
   // u = LN(x) ; logits = u E^T in fp32
-  MTNLG_TRY(mtnlg_layernorm_fwd(dt, T, h, x, nullptr, nullptr, ln_g, ln_b, desc->ln_eps, nullptr, u, mean, rstd, st));
+  MTNLG_TRY(mtnlg_layernorm_fwd(dt, T, h, x, nullptr, nullptr, ln_g, ln_b, eps, nullptr, u, mean, rstd, st));
   MTNLG_TRY(mtnlg_gemm(dt, MTNLG_GEMM_NT, T, Vl, h, u, emb, logits, nullptr, nullptr, MTNLG_EPI_OUT_F32, gws, W.gemm_bytes, st));
   // softmax statistics, with the three exchanges of a vocabulary-sliced group
   {

@@ -54,3 +54,16 @@ def paper_iteration_flops(batch, seq, layers, hidden, vocab):
 def boundary_activation_bytes(batch, layers, seq, hidden, bytes_per=2):
     """Section 2.1, "Memory Efficiency": batch x layers x seq x hidden x 2 bytes."""
     return batch * layers * seq * hidden * bytes_per
+
+
+def hbm_bytes_per_launch(wl, bytes_per=2):
+    """Algorithmic HBM bytes of one launch of each bandwidth-bound kernel class on workload ``wl`` (every operand
+    read once, every result written once; statistics, gains and biases are negligible and not counted):
+      LayerNorm forward   x in, LN(x) out                              2 T h
+      LayerNorm backward  x, d(out), residual gradient in, dx out      4 T h   (its column sums are by-products)
+      GeLU backward       z, dg in, dz out                             3 T F
+      column sums         the matrix in; three per layer (T x h, T x F, T x 3p), averaged over a layer's launches
+    in elements, times ``bytes_per``."""
+    T, h, p, F = wl.tokens, wl.hidden, wl.heads * wl.head_dim, wl.ffn
+    return {"ln_fwd": 2 * T * h * bytes_per, "ln_bwd": 4 * T * h * bytes_per, "gelu": 3 * T * F * bytes_per,
+            "colsum": T * (h + F + 3 * p) * bytes_per / 3.0}

@@ -1,5 +1,25 @@
 """Shared helpers of the GPU parity tests: conversions between device tensors and the oracle's
-fp64 numpy arrays, and the error measure (relative Frobenius error per output tensor)."""
+fp64 numpy arrays, and the two error measures every compared tensor has to pass.
+
+1. Relative Frobenius error per output tensor, ||got - want||_F / ||want||_F <= tol, with tol = 1e-2 on the
+   bf16 path and 1e-5 on the fp32 path (the stated bar; TOL below).
+2. An element-wise complement, because one norm per tensor cannot see a small wrong region (one wrong 16 x 16
+   block of a 2048 x 20480 output moves the norm by 2.5e-3): every element must satisfy
+       |got - want| <= ELEM_SIGMAS * tol * (rms(want) + |want|).
+   An error field at the bar has an additive part (accumulated roundings of the operands: standard deviation
+   tol * rms(want)) and a part proportional to the element (roundings of the element itself and of factors it is
+   proportional to: relative standard deviation tol); were they Gaussian, none of up to 1e9 compared elements
+   would leave 6 standard deviations of either.  They are sums of products of roundings and values, heavier-tailed
+   than that: the largest excursion measured over all comparisons of the suite is 6.9 (a weight gradient of
+   1.6e8 elements summed over a 12-token prefix, relative Frobenius error 5e-3), so the allowance is 8.  A
+   misplaced tile or a bad edge row is wrong by about rms(want) per element where |want| is about rms(want): six
+   times the allowance at the bf16 bar.
+
+Every comparison is recorded (test id, tensor, both measures); conftest.py prints the worst ones at the end of a
+run and writes the whole table to $MTNLG_PARITY_LOG when that is set.
+"""
+import os
+
 import numpy as np
 import torch
 
@@ -7,6 +27,9 @@ import oracle
 
 # spec tolerances: relative Frobenius error per output tensor
 TOL = {"fp32": 1e-5, "bf16": 1e-2}
+ELEM_SIGMAS = 8.0
+
+RECORDS = []   # (test id, what, rel_fro, tol, elementwise ratio: worst |diff| / allowance, elements)
 
 
 def to_np(t):
@@ -23,11 +46,55 @@ def rel_fro(got, want):
     return float(num / den)
 
 
-def assert_close(got, want, tol, what):
+def elementwise_ratio(got, want, tol):
+    """max over elements of |got - want| / (ELEM_SIGMAS * tol * (rms(want) + |want|)); <= 1 passes."""
+    got = to_np(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64).reshape(got.shape)
+    if want.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(want * want)))
+    allow = ELEM_SIGMAS * tol * (rms + np.abs(want))
+    diff = np.abs(got - want)
+    if rms == 0.0:
+        return 0.0 if not diff.any() else float("inf")
+    return float((diff / allow).max())
+
+
+def assert_close(got, want, tol, what, elementwise=True):
     assert torch.isfinite(got.float()).all() if isinstance(got, torch.Tensor) else True, f"{what}: non-finite"
     err = rel_fro(got, want)
+    ratio = elementwise_ratio(got, want, tol) if elementwise else float("nan")
+    test = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
+    RECORDS.append((test, what, err, tol, ratio, int(np.asarray(want).size)))
     assert err <= tol, f"{what}: relative Frobenius error {err:.3e} > {tol:.1e}"
+    if elementwise:
+        assert ratio <= 1.0, f"{what}: an element is off by {ratio:.2f} x its allowance (tol {tol:.1e})"
     return err
+
+
+def poison(run):
+    """NaN (all-ones words) in every byte the library writes before it reads -- saved activations, workspace,
+    outputs of a LayerRunner / StageRunner: a kernel that reads scratch it has not filled, or leaves a hole in an
+    output, then shows up as a non-finite result."""
+    for buf in (run.saved, run.workspace):
+        buf.view(torch.int32).fill_(-1)      # sizes are multiples of 256 bytes; 0xFFFFFFFF is NaN as bf16 and as float
+    run.y.fill_(float("nan"))
+    run.dx.fill_(float("nan"))
+    return run
+
+
+def copy_into_pointer(ptr, src):
+    """Copy a contiguous device tensor over the device memory at address `ptr` (what an exchange hook does with the
+    group's value) and wait for it: src may be freed by the caller right after."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    rc = hip.hipMemcpyAsync(ctypes.c_void_p(ptr), ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                            3, stream)
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpyAsync failed: {rc}")
+    torch.cuda.current_stream().synchronize()
 
 
 def oracle_dims(wl, gelu_exact=False, softmax_scale=0.0, ln_eps=1e-5):
