@@ -32,7 +32,8 @@
  * Descriptor / weight-table / grad-table structs themselves live in HOST memory.
  * The library allocates no device memory, launches only on the stream it is
  * given and never synchronises the host.  Its only process-wide state: per-device
- * marks that a kernel's attributes have been set and the optional timing record.
+ * marks that a kernel's attributes have been set, the address of the static
+ * array of mtnlg_colsum_static, and the optional timing record.
  *
  * Layouts (row-major everywhere):
  *   activations  [micro_batch, seq, hidden], hidden contiguous
@@ -257,6 +258,16 @@ int mtnlg_gelu_bwd(int dtype, int gelu, int64_t count, const void *z, const void
 size_t mtnlg_colsum_workspace(int64_t T, int64_t C);
 int mtnlg_colsum(int dtype, int64_t T, int64_t C, const void *in, void *out, int out_f32,
                  int accumulate, void *workspace, void *stream);
+/* mtnlg_colsum for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same
+ * kernels, same result bit for bit.  The partial sums go through a 4 MiB array that the library holds on every
+ * GPU it has run this call on until the process ends; the call allocates and frees nothing.
+ * Limit: C <= mtnlg_colsum_static_max_columns() (32768), beyond that MTNLG_WORKSPACE_TOO_SMALL.  Every call on a
+ * GPU shares that GPU's array: calls that overlap on one GPU (different streams or threads) race; calls on one
+ * stream are ordered.  Other errors as mtnlg_colsum; MTNLG_HIP_ERROR also if the array's address cannot be had. */
+int64_t mtnlg_colsum_static_max_columns(void);
+int mtnlg_colsum_static(int dtype, int64_t T, int64_t C, const void *in, void *out, int out_f32, int accumulate,
+                        void *stream);
 /* out = res + partial + bias[col] over [T,h] (bias nullable). */
 int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const void *partial,
                         const void *bias, void *out, void *stream);

@@ -117,6 +117,8 @@ def lib():
             "mtnlg_gelu_bwd": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp]),
             "mtnlg_colsum_workspace": (sz, [i64, i64]),
             "mtnlg_colsum": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp]),
+            "mtnlg_colsum_static_max_columns": (i64, []),
+            "mtnlg_colsum_static": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp]),
             "mtnlg_bias_residual": (ctypes.c_int, [ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]),
             "mtnlg_calibrate_mfma_operand_bytes": (sz, [ctypes.c_int]),
             "mtnlg_calibrate_mfma_flops": (i64, [ctypes.c_int, ctypes.c_int]),
@@ -137,7 +139,8 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_layer_bwd", "mtnlg_stage_step", "mtnlg_stage_step_accumulate", "mtnlg_gemm_workspace", "mtnlg_gemm", "mtnlg_layernorm_fwd",
             "mtnlg_layernorm_bwd_workspace", "mtnlg_layernorm_bwd", "mtnlg_attention_fwd",
             "mtnlg_attention_bwd_workspace", "mtnlg_attention_bwd", "mtnlg_gelu_fwd", "mtnlg_gelu_bwd",
-            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
+            "mtnlg_colsum_workspace", "mtnlg_colsum", "mtnlg_colsum_static_max_columns", "mtnlg_colsum_static",
+            "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
             "mtnlg_lm_head_workspace", "mtnlg_embedding_fwd", "mtnlg_embedding_bwd", "mtnlg_lm_head_step",
             "mtnlg_calibrate_mfma_operand_bytes", "mtnlg_calibrate_mfma_flops", "mtnlg_calibrate_mfma",
             "mtnlg_calibrate_copy", "mtnlg_profile_enable", "mtnlg_profile_read")
@@ -361,6 +364,16 @@ def mtnlg_colsum(x, out, workspace, accumulate=False):
     T, C = x.shape
     _check(lib().mtnlg_colsum(_dtype_code(x), T, C, _p(x), _p(out), int(out.dtype == torch.float32),
                               int(accumulate), _p(workspace), _stream()), "mtnlg_colsum")
+
+
+def mtnlg_colsum_static_max_columns():
+    return lib().mtnlg_colsum_static_max_columns()
+
+
+def mtnlg_colsum_static(x, out, accumulate=False):
+    T, C = x.shape
+    _check(lib().mtnlg_colsum_static(_dtype_code(x), T, C, _p(x), _p(out), int(out.dtype == torch.float32),
+                                     int(accumulate), _stream()), "mtnlg_colsum_static")
 
 
 def mtnlg_bias_residual(res, partial, bias, out):

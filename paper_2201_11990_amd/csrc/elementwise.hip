@@ -3,6 +3,8 @@
 // backward, bias + residual, and the column reductions that produce bias and
 // LayerNorm parameter gradients.  All arithmetic fp32; 16-byte (bf16) or
 // 32-byte (float) accesses per lane, consecutive lanes on consecutive addresses.
+#include <mutex>
+
 #include "common.h"
 
 namespace mtnlg {
@@ -536,7 +538,49 @@ int mtnlg_bias_residual(int dtype, int64_t T, int64_t h, const void *res, const 
   return check_launch();
 }
 
-}  // extern "C"
-
+// ---- column sum for callers that cannot allocate device memory -------------------------------------------
+// Same kernels as mtnlg_colsum; the stage-1 partials ([row blocks <= 32][C] floats) live in a file-scope device
+// array instead of a caller's workspace.  Every GPU the library runs on holds its own copy of the array (4 MiB)
+// at its own address until the process ends; in host code the array's name is only a handle, so the address is
+// asked for once per device (with that device current) and kept.
 namespace mtnlg {
+constexpr int64_t COLSUM_STATIC_MAX_COLS = 32768;
+constexpr int COLSUM_STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) float scratch[32 * COLSUM_STATIC_MAX_COLS];
+
+static std::mutex g_scratch_mutex;
+static float *g_scratch_ptr[COLSUM_STATIC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, nullptr on failure.
+static float *scratch_on_current_device() {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= COLSUM_STATIC_MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    float *ptr = nullptr;
+    if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[device] = ptr;
+  }
+  return g_scratch_ptr[device];
+}
 }  // namespace mtnlg
+
+int64_t mtnlg_colsum_static_max_columns(void) { return COLSUM_STATIC_MAX_COLS; }
+
+int mtnlg_colsum_static(int dtype, int64_t T, int64_t C, const void *in, void *out, int out_f32, int accumulate,
+                        void *stream) {
+  if (!in || !out) return MTNLG_NULL_POINTER;
+  if (T <= 0 || C <= 0) return MTNLG_INVALID_ARG;
+  if (dtype != MTNLG_F32 && dtype != MTNLG_BF16) return MTNLG_INVALID_ARG;
+  if (C % 8) return MTNLG_UNSUPPORTED_SHAPE;
+  if (C > COLSUM_STATIC_MAX_COLS) return MTNLG_WORKSPACE_TOO_SMALL;   // the partials would not fit the static array
+  float *ptr = scratch_on_current_device();
+  if (!ptr) return MTNLG_HIP_ERROR;
+  // Stage 1 writes every partial that stage 2 reads ([row blocks][C], all columns < C), so nothing in the array
+  // has to start at zero and what an earlier, larger call left behind is never read.
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MTNLG_F32) return colsum_launch<float>(T, C, in, out, 1, accumulate, ptr, st);
+  return colsum_launch<bf16>(T, C, in, out, out_f32, accumulate, ptr, st);
+}
+
+}  // extern "C"
