@@ -209,11 +209,14 @@ enum mtnlg_gemm_layout {
 #define MTNLG_EPI_RESIDUAL 4u   /* + aux[m,n] (same shape/ld as C) read                 */
 #define MTNLG_EPI_ACCUMULATE 8u /* C += result                                          */
 #define MTNLG_EPI_OUT_F32 16u   /* C is float even when inputs are bf16                 */
-#define MTNLG_EPI_GELU_ERF 32u  /* with MTNLG_EPI_GELU: erf form instead of tanh form   */
+#define MTNLG_EPI_GELU_ERF 32u  /* with MTNLG_EPI_GELU / _GELU_GRAD: erf form, not tanh   */
+#define MTNLG_EPI_GELU_GRAD 64u /* C = acc * GeLU'(aux[m,n]): the activation's backward
+                                   fused into the product that yields dg (aux = z, read)  */
 
 /* General matrix product with fp32 accumulation, dense row-major operands
  * (leading dimension = row length).  dtype selects float or bf16 inputs.
- * aux: pre-activation output under EPI_GELU, residual input under EPI_RESIDUAL.
+ * aux: pre-activation output under EPI_GELU, residual input under EPI_RESIDUAL, pre-activation input under
+ * EPI_GELU_GRAD (at most one of the three; EPI_GELU_GRAD goes with neither bias nor accumulate).
  * workspace (nullable): mtnlg_gemm_workspace() bytes of scratch that lets a problem
  * whose last round of output tiles would leave most compute units idle split those
  * tiles along K; without it the same result is computed by whole tiles only. */

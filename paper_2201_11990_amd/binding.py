@@ -19,7 +19,7 @@ F32, BF16 = 0, 1
 GELU_TANH, GELU_ERF = 0, 1
 RECOMPUTE, ACCUMULATE_WGRAD, WGRAD_FP32 = 1, 2, 4
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
-EPI_BIAS, EPI_GELU, EPI_RESIDUAL, EPI_ACCUMULATE, EPI_OUT_F32, EPI_GELU_ERF = 1, 2, 4, 8, 16, 32
+EPI_BIAS, EPI_GELU, EPI_RESIDUAL, EPI_ACCUMULATE, EPI_OUT_F32, EPI_GELU_ERF, EPI_GELU_GRAD = 1, 2, 4, 8, 16, 32, 64
 KERNEL_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd",
                   "gelu", "colsum", "elementwise")
 

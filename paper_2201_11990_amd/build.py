@@ -22,7 +22,10 @@ def _compile(src):
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    # expected and harmless: the host pass does not know the packed-fp32 feature; the code generator remarks on M0 in
+    # the clobber lists of the LDS-DMA asm statements (csrc/common.h says why it is there)
+    quiet = ("packed-fp32-ops", "clobber list contains reserved registers", "Reserved registers on the clobber list")
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(q in l for q in quiet))
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():

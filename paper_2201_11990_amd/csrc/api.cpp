@@ -99,11 +99,12 @@ void work_layout(const Shape &S, Work *W) {
   W->pong = c.take(S.T * S.h * S.es);
   // split-K scratch: the largest need over the layer's twelve GEMMs
   size_t gw = 0;
-  const int64_t shapes[12][3] = {{S.T, 3 * S.p, S.h}, {S.T, S.h, S.p}, {S.T, S.F, S.h}, {S.T, S.h, S.F},
-                                 {S.T, S.F, S.h}, {S.T, S.h, S.F}, {S.T, S.p, S.h}, {S.T, S.h, 3 * S.p},
-                                 {S.h, S.F, S.T}, {S.F, S.h, S.T}, {S.h, S.p, S.T}, {3 * S.p, S.h, S.T}};
-  for (auto &sh : shapes) {
-    size_t b = mtnlg_gemm_workspace(S.dtype, MTNLG_GEMM_NT, sh[0], sh[1], sh[2]);
+  const int64_t shapes[12][3] = {{S.T, 3 * S.p, S.h}, {S.T, S.h, S.p}, {S.T, S.F, S.h}, {S.T, S.h, S.F},   // forward
+                                 {S.T, S.F, S.h}, {S.T, S.h, S.F}, {S.T, S.p, S.h}, {S.T, S.h, 3 * S.p},   // input gradients
+                                 {S.h, S.F, S.T}, {S.F, S.h, S.T}, {S.h, S.p, S.T}, {3 * S.p, S.h, S.T}};  // weight gradients
+  for (int i = 0; i < 12; ++i) {
+    const int layout = i < 4 ? MTNLG_GEMM_NT : i < 8 ? MTNLG_GEMM_NN : MTNLG_GEMM_TN;
+    size_t b = mtnlg_gemm_workspace(S.dtype, layout, shapes[i][0], shapes[i][1], shapes[i][2]);
     if (b > gw) gw = b;
   }
   W->gemm_bytes = gw;
@@ -196,12 +197,12 @@ int layer_bwd_impl(const Shape &S, const mtnlg_layer_weights *w, const void *x, 
   const int g32 = S.g32 ? 1 : 0, acc = S.acc ? 1 : 0;
   const uint32_t wg_epi = (S.acc ? MTNLG_EPI_ACCUMULATE : 0u) | ((S.g32 && S.dtype == MTNLG_BF16) ? MTNLG_EPI_OUT_F32 : 0u);
 
-  // y = x1 + M + b2:  db2 = sum_t dy ; dg = dy W2 ; dW2 = dy^T g
+  // y = x1 + M + b2:  db2 = sum_t dy ; dW2 = dy^T g ; dz = (dy W2) o GeLU'(z), the activation's backward in the
+  // epilogue of the product (dg itself is never stored) ; db1 = sum_t dz
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.h, dy, G->b_fc2, g32, acc, red, st));
-  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.F, S.h, dy, w->w_fc2, dgz, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_TN, S.h, S.F, S.T, dy, g, G->w_fc2, nullptr, nullptr, wg_epi, gws, W.gemm_bytes, st));
-  // dz = dg o GeLU'(z) ; db1 = sum_t dz
-  MTNLG_TRY(mtnlg_gelu_bwd(S.dtype, S.gelu_erf, S.T * S.F, z, dgz, dgz, st));
+  MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.F, S.h, dy, w->w_fc2, dgz, nullptr, const_cast<void *>(z),
+                       MTNLG_EPI_GELU_GRAD | (S.gelu_erf ? MTNLG_EPI_GELU_ERF : 0u), gws, W.gemm_bytes, st));
   MTNLG_TRY(mtnlg_colsum(S.dtype, S.T, S.F, dgz, G->b_fc1, g32, acc, red, st));
   // du2_r = dz W1 ; dW1 = dz^T u2
   MTNLG_TRY(mtnlg_gemm(S.dtype, MTNLG_GEMM_NN, S.T, S.h, S.F, dgz, w->w_fc1, du, nullptr, nullptr, 0, gws, W.gemm_bytes, st));
@@ -365,8 +366,8 @@ int mtnlg_stage_step_accumulate(const mtnlg_layer_desc *desc, int n_layers, cons
 }
 
 size_t mtnlg_gemm_workspace(int dtype, int layout, int64_t M, int64_t N, int64_t K) {
-  (void)layout;
-  return dtype == MTNLG_BF16 ? gemm_mfma_workspace_bytes(M, N, K) : 0;
+  if (layout < 0 || layout > 2) return 0;
+  return dtype == MTNLG_BF16 ? gemm_mfma_workspace_bytes(layout, M, N, K) : 0;
 }
 
 int mtnlg_gemm(int dtype, int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
@@ -376,8 +377,14 @@ int mtnlg_gemm(int dtype, int layout, int64_t M, int64_t N, int64_t K, const voi
   if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return MTNLG_INVALID_ARG;
   if (dtype != MTNLG_F32 && dtype != MTNLG_BF16) return MTNLG_INVALID_ARG;
   if ((epilogue & MTNLG_EPI_BIAS) && !bias) return MTNLG_NULL_POINTER;
-  if ((epilogue & (MTNLG_EPI_GELU | MTNLG_EPI_RESIDUAL)) && !aux) return MTNLG_NULL_POINTER;
+  if (epilogue & ~(MTNLG_EPI_BIAS | MTNLG_EPI_GELU | MTNLG_EPI_RESIDUAL | MTNLG_EPI_ACCUMULATE | MTNLG_EPI_OUT_F32 |
+                   MTNLG_EPI_GELU_ERF | MTNLG_EPI_GELU_GRAD))
+    return MTNLG_INVALID_ARG;
+  if ((epilogue & (MTNLG_EPI_GELU | MTNLG_EPI_RESIDUAL | MTNLG_EPI_GELU_GRAD)) && !aux) return MTNLG_NULL_POINTER;
   if ((epilogue & MTNLG_EPI_GELU) && (epilogue & (MTNLG_EPI_RESIDUAL | MTNLG_EPI_ACCUMULATE | MTNLG_EPI_OUT_F32)))
+    return MTNLG_INVALID_ARG;
+  if ((epilogue & MTNLG_EPI_GELU_GRAD) &&
+      (epilogue & (MTNLG_EPI_GELU | MTNLG_EPI_RESIDUAL | MTNLG_EPI_ACCUMULATE | MTNLG_EPI_BIAS)))
     return MTNLG_INVALID_ARG;
   if (dtype == MTNLG_F32) epilogue &= ~MTNLG_EPI_OUT_F32;
   hipStream_t st = (hipStream_t)stream;

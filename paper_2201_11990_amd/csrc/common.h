@@ -137,6 +137,8 @@ __device__ __forceinline__ void epilogue_store(const EpiArgs &ea, void *C, int64
     acc = gelu_f(acc, (ea.flags & MTNLG_EPI_GELU_ERF) != 0);
   }
   if (ea.flags & MTNLG_EPI_RESIDUAL) acc += to_f32(static_cast<const E *>(ea.aux)[m * ldc + n]);
+  if (ea.flags & MTNLG_EPI_GELU_GRAD)
+    acc *= gelu_grad_f(to_f32(static_cast<const E *>(ea.aux)[m * ldc + n]), (ea.flags & MTNLG_EPI_GELU_ERF) != 0);
   if (ea.flags & MTNLG_EPI_OUT_F32) {
     float *c = static_cast<float *>(C) + m * ldc + n;
     *c = (ea.flags & MTNLG_EPI_ACCUMULATE) ? *c + acc : acc;
@@ -185,12 +187,15 @@ int gemm_generic(int dtype, int layout, int64_t M, int64_t N, int64_t K, const v
 // returns MTNLG_UNSUPPORTED_SHAPE when the MFMA kernel cannot take this problem
 // ws (nullable): scratch for the split-K tail, see gemm_mfma_workspace_bytes
 // prof_class: kernel class the launch is timed under (-1: MTNLG_K_GEMM_NT + layout)
+// tile: one of gemm_tile, or -1 to let gemm_mfma_pick_tile choose (what every product call does)
+enum gemm_tile { GEMM_TILE_GENERAL_256 = 0, GEMM_TILE_GENERAL_128, GEMM_TILE_STREAM_256x256, GEMM_TILE_STREAM_256x320 };
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B,
                    void *C, const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes,
-                   hipStream_t stream, int prof_class = -1);
+                   hipStream_t stream, int prof_class = -1, int tile = -1);
+int gemm_mfma_pick_tile(int layout, int64_t M, int64_t N, int64_t K, bool have_workspace);
 // true when the problem takes the streaming kernel (aligned M, N, K)
-bool gemm_mfma_streams(int64_t M, int64_t N, int64_t K);
-size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K);
+bool gemm_mfma_streams(int layout, int64_t M, int64_t N, int64_t K);
+size_t gemm_mfma_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K);
 int attention_fwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
                          void *a, float *lse, hipStream_t stream);
 int attention_bwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,

@@ -26,6 +26,8 @@
 //
 // Workgroups are numbered so that the 8 XCDs (workgroup id mod 8) each own a contiguous run of
 // column-major tiles: neighbours in an XCD's L2 share A and B panels.
+#include <type_traits>
+
 #include "common.h"
 
 namespace mtnlg {
@@ -33,6 +35,8 @@ namespace mtnlg {
 namespace {
 
 constexpr int BK = 64;
+// Relative cost per FLOP of the wider streaming tile against 256 x 256 (measured on the MT-NLG slice's shapes).
+constexpr double GEMM_COST_256x320 = 0.97;
 
 struct GemmArgs {
   int64_t M, N, K;
@@ -226,6 +230,12 @@ __device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t 
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
+  if (flags & MTNLG_EPI_GELU_GRAD) {
+    load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
+    const bool erf_form = (flags & MTNLG_EPI_GELU_ERF) != 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(t[e], erf_form);
+  }
   if (flags & MTNLG_EPI_OUT_F32) {
     float *c = static_cast<float *>(g.C) + off;
     if (flags & MTNLG_EPI_ACCUMULATE) {
@@ -418,32 +428,59 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 }
 
 // =======================================================================================
-// Streaming kernel: 256x256 tile, BK = 64, both operands brought global -> LDS by DMA
-// (buffer_load ... lds), no register staging, no LDS store instructions; MFMA 16x16x32.
-//   A lives in a ring of two 32 KB stages, B in a ring of three (B is the operand that comes
-//   from HBM for the first time: the weights); the DMA instructions of a slab are spread over
-//   the four phases of a slab (two per phase and wave) so that the texture path never sees a burst.
-//   K-contiguous operand: stage = [256 rows][128 B], 16-byte chunk c of row r at chunk position
+// Streaming kernel: 256 x BN tile (BN 256 or 320) on 2 x 4 waves, BK = 64, both operands brought
+// global -> LDS by DMA (buffer_load ... lds), no register staging, no LDS store instructions; MFMA 16x16x32.
+//   Tile shapes and LDS rings (160 KB per compute unit; a stage is ROWS x 128 bytes):
+//     256 x 256: A in a ring of two 32 KB stages, B in a ring of three (B is the operand that comes from HBM
+//                for the first time: the weights); 160 KB.
+//     256 x 320: A two stages of 32 KB, B two of 40 KB; 144 KB.   N a multiple of 320.
+//   The wider tile moves 10 % fewer operand bytes per FLOP from L2 into LDS ((BM + BN) / (BM BN)), which is
+//   what holds the clock down under the board's power limit, and it covers the layer's forward and
+//   input-gradient shapes in whole rounds of 256 tiles; it pays with a ring one stage shorter and with 160 of
+//   a wave's 256 registers in accumulators (a 320 x 320 tile would need 200 and does not fit).
+//   The DMA instructions of a slab are spread over the phases of a slab so that the texture path never sees a burst.
+//   K-contiguous operand: stage = [ROWS][128 B], 16-byte chunk c of row r at chunk position
 //     c ^ (r & 7); MFMA fragments are 16-byte LDS reads (this placement measured conflict-free for the
 //     fragment pattern -- 16 rows x one chunk per 16 lanes -- at 4.5-4.9 cycles per wave instruction;
 //     with a further ^ (r >> 3), which a model of 16 consecutive lanes per LDS pass asks for, the
 //     same reads take 7.8).
-//   Row-contiguous operand ([k][row] in memory): stage = [64 k][512 B] as in memory, with the
-//     16-byte unit u of k-row k at unit position (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
+//   Row-contiguous operand ([k][row] in memory): stage = [64 k][ROWS x 2 B] as in memory, with the 16-byte units
+//     of a k-row permuted (tr_pos below) so that the fragment reads spread over all banks;
 //     MFMA fragments are two transposing 8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads
 //     4 k-rows x 16 rows and every lane receives the 4 k values of its own row).
-//   A slab is four phases of 16 MFMAs: (k-step 0, rows 0-63 of the wave tile), (0, rows 64-127),
-//   (1, rows 0-63), (1, rows 64-127); each phase loads the fragments of the next one.  The one
+//   A slab is four phases: (k-step 0, first half of the wave tile's rows), (0, second half), (1, first),
+//   (1, second); each phase loads the fragments of the next one.  The one
 //   workgroup barrier per slab sits before the last phase (whose fragments are already in
 //   registers) so that the first fragment reads of the next slab hide behind a phase of MFMAs.
-//   Aligned problems only: M, N multiples of 256, K of 64.
-template <bool AT, bool BT, bool PLAIN16>
+//   Aligned problems only: M a multiple of BM, N of BN, K of 64.
+
+// Position of the 16-byte unit u of k-row k inside a row-contiguous stage's k-row of UPR units (an involution
+// in u for every k).  A transposing fragment read touches, per 16-lane group, k-rows k0 .. k0+3 (k0 a multiple
+// of 4) at two neighbouring units, and the four groups of a wave sit 8 k-rows apart.
+//   32 units (512-byte k-rows, every k-row starts on the same bank): k & 3 moves the 64-byte group, k bit 3 the
+//     32-byte pair inside it.
+//   40 units (640-byte k-rows: consecutive k-rows already sit half the bank space apart): k bit 1 and k bit 3
+//     move the 32-byte pair inside the aligned 128-byte group, which keeps units 32 .. 39 in place.
+template <int UPR>
+__device__ __forceinline__ int tr_pos(int u, int k) {
+  if constexpr (UPR == 32) return (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
+  else return (u & ~7) | ((u & 7) ^ ((k & 2) | ((k >> 1) & 4)));
+}
+
+template <int N>
+__device__ __forceinline__ void wait_dma_and_barrier() {   // at most N of this wave's DMAs still in flight
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, bool AT, bool BT, bool PLAIN16>
 __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int BM = 256, BN = 256, WGM = 2, WGN = 4, NWAVES = WGM * WGN;
+  constexpr int WGM = 2, WGN = 4, NWAVES = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 16, TN = WN / 16, HM = TM / 2;
-  constexpr int STAGE = 256 * BK * 2, A_RING = 2 * STAGE, B_RING = 3 * STAGE;
-  constexpr int NI = 32 / NWAVES;   // DMA instructions per wave per operand and slab
+  constexpr int A_STAGE = BM * BK * 2, B_STAGE = BN * BK * 2;
+  constexpr int RING_B = (BM == 256 && BN == 256) ? 3 : 2;
+  constexpr int A_RING = 2 * A_STAGE, B_RING = RING_B * B_STAGE;
+  constexpr int NIA = BM / 8 / NWAVES, NIB = BN / 8 / NWAVES;   // DMA instructions (1 KB each) per wave, operand and slab
   const int nk_all = (int)(g.K / BK);
   int pid, slab0 = 0, slab1 = nk_all, part_id = -1;
   if ((int)blockIdx.x < 8 * g.per_xcd) {
@@ -464,28 +501,29 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   const bf16 *Abase = AT ? g.A + m0 : g.A + m0 * g.lda;
   const bf16 *Bbase = BT ? g.B + n0 : g.B + n0 * g.ldb;
 
-  // DMA addressing.  Wave w issues instructions q = NI w .. NI w + NI - 1 of each operand; instruction
-  // q fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l the 16 bytes at 16 l.
-  auto dma_offset = [&](int q, int64_t ld, bool transposed) -> uint32_t {
+  // DMA addressing.  Instruction q of an operand fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l
+  // the 16 bytes at 16 l; wave w issues the instructions NI w .. NI w + NI - 1.
+  auto dma_offset = [&](int q, int64_t ld, bool transposed, int rows) -> uint32_t {
     if (!transposed) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
       const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3);   // row % 8 == lane / 8
       return (uint32_t)(row * ld * 2 + c * 16);
-    } else {             // k-rows 2q, 2q+1, lane l: k = 2q + l/32, unit position l%32
-      const int k = 2 * q + (lane >> 5), p = lane & 31;
-      const int u = (((p >> 2) ^ (k & 3)) << 2) | ((p & 3) ^ ((k >> 2) & 2));
+    } else {             // unit 64 q + l of the stage: k-row (64 q + l) / UPR, position (64 q + l) % UPR
+      const int upr = rows / 8, i = 64 * q + lane;
+      const int k = i / upr, pos = i % upr;
+      const int u = upr == 32 ? tr_pos<32>(pos, k) : tr_pos<40>(pos, k);
       return (uint32_t)(k * ld * 2 + u * 16);
     }
   };
-  uint32_t a_off[NI], b_off[NI];
+  uint32_t a_off[NIA], b_off[NIB];
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    a_off[i] = dma_offset(wave * NI + i, g.lda, AT);
-    b_off[i] = dma_offset(wave * NI + i, g.ldb, BT);
-  }
+  for (int i = 0; i < NIA; ++i) a_off[i] = dma_offset(wave * NIA + i, g.lda, AT, BM);
+#pragma unroll
+  for (int i = 0; i < NIB; ++i) b_off[i] = dma_offset(wave * NIB + i, g.ldb, BT, BN);
   // With a transposing LDS read in the loop the DMA goes out as inline assembly (see dma16: the
   // compiler would put a wait for all memory operations in front of those reads); otherwise
   // through the builtin, which the scheduling hints below can place.
-  auto issue = [&](const bf16 *base, const uint32_t(&off)[NI], char *stage, int i0, int i1) {
+  auto issue = [&](const bf16 *base, const auto &off, char *stage, int i0, int i1) {
+    constexpr int NI = sizeof(off) / sizeof(off[0]);
     char *dst = stage + wave * (NI * 1024);
     if constexpr (AT || BT) {
       const dma_rsrc_t rs = dma_rsrc(base);
@@ -515,7 +553,7 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
 
   // MFMA 16x16x32 operand of the 16-row block at r0 for k-step kk (32 k): lane l holds row
   // r0 + l%16, k = 32 kk + 8 (l/16) .. + 7
-  auto frag = [&](const char *stage, int r0, int kk, bool transposed) -> bf16x8 {
+  auto frag = [&](const char *stage, int r0, int kk, bool transposed, int rows) -> bf16x8 {
     if (!transposed) {
       const int row = r0 + (lane & 15);
       return *reinterpret_cast<const bf16x8 *>(stage + row * 128 + (((kk * 4 + (lane >> 4)) ^ (row & 7)) << 4));
@@ -526,8 +564,8 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
       const int kbase = 32 * kk + 8 * grp + (L >> 2);
       auto addr = [&](int k) {
         const int u = nb >> 3;                                    // 16-byte unit of the row
-        const int p = (((u >> 2) ^ (k & 3)) << 2) | ((u & 3) ^ ((k >> 2) & 2));
-        return stage + k * 512 + p * 16 + (nb & 7) * 2;
+        const int p = rows == 256 ? tr_pos<32>(u, k) : tr_pos<40>(u, k);
+        return stage + k * (rows * 2) + p * 16 + (nb & 7) * 2;
       };
       const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)addr(kbase));
       const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)addr(kbase + 4));
@@ -538,11 +576,11 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   bf16x8 af[2][HM], bfr[2][TN];   // A: one buffer per half of the wave tile; B: one per k-step parity
   auto read_a = [&](const char *abuf, int kk, int h) {
 #pragma unroll
-    for (int i = 0; i < HM; ++i) af[h][i] = frag(abuf, wm * WM + (h * HM + i) * 16, kk, AT);
+    for (int i = 0; i < HM; ++i) af[h][i] = frag(abuf, wm * WM + (h * HM + i) * 16, kk, AT, BM);
   };
   auto read_b = [&](const char *bbuf, int kk) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[kk & 1][j] = frag(bbuf, wn * WN + j * 16, kk, BT);
+    for (int j = 0; j < TN; ++j) bfr[kk & 1][j] = frag(bbuf, wn * WN + j * 16, kk, BT, BN);
   };
   auto mfma_phase = [&](int kk, int h) {
 #pragma unroll
@@ -556,55 +594,101 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   const int nk = slab1 - slab0;
   auto slab_k = [&](int it) { return (int64_t)(slab0 + (it < nk ? it : nk - 1)) * BK; };
   char *const aring = smem, *const bring = smem + A_RING;
-  // prologue: A slab 0, B slabs 0 and 1, first half of A slab 1
-  issue(a_at(slab_k(0)), a_off, aring, 0, NI);
-  issue(b_at(slab_k(0)), b_off, bring, 0, NI);
-  issue(b_at(slab_k(1)), b_off, bring + STAGE, 0, NI);
-  issue(a_at(slab_k(1)), a_off, aring + STAGE, 0, NI / 2);
-  asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");   // A 0, B 0 landed
-  read_a(aring, 0, 0);
-  read_b(bring, 0);
-
   constexpr int RA = (AT ? 2 : 1) * HM, RB = (BT ? 2 : 1) * TN;   // LDS read instructions of an A half / of B
   int a_cur = 0, b_cur = 0;   // ring offsets of slab `it`
-  for (int it = 0; it < nk; ++it) {
-    const int a_nxt = a_cur ^ STAGE;
-    const int b_nxt = b_cur + STAGE >= B_RING ? b_cur + STAGE - B_RING : b_cur + STAGE;
-    const int b_nn = b_nxt + STAGE >= B_RING ? b_nxt + STAGE - B_RING : b_nxt + STAGE;
-    // phase 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
-    // phases 1, 2: B slab it+2 into the ring stage that held slab it-1
-    // phase 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
+
+  if constexpr (RING_B == 3) {
+    // prologue: A slab 0, B slabs 0 and 1, first half of A slab 1
+    issue(a_at(slab_k(0)), a_off, aring, 0, NIA);
+    issue(b_at(slab_k(0)), b_off, bring, 0, NIB);
+    issue(b_at(slab_k(1)), b_off, bring + B_STAGE, 0, NIB);
+    issue(a_at(slab_k(1)), a_off, aring + A_STAGE, 0, NIA / 2);
+    wait_dma_and_barrier<NIB + NIA / 2>();   // A 0, B 0 landed
+    read_a(aring, 0, 0);
+    read_b(bring, 0);
+    for (int it = 0; it < nk; ++it) {
+      const int a_nxt = a_cur ^ A_STAGE;
+      const int b_nxt = b_cur + B_STAGE >= B_RING ? b_cur + B_STAGE - B_RING : b_cur + B_STAGE;
+      const int b_nn = b_nxt + B_STAGE >= B_RING ? b_nxt + B_STAGE - B_RING : b_nxt + B_STAGE;
+      // phase 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
+      // phases 1, 2: B slab it+2 into the ring stage that held slab it-1
+      // phase 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
 #pragma unroll
-    for (int ph = 0; ph < 4; ++ph) {
-      const int kk = ph >> 1, h = ph & 1;
-      // The two waves of a SIMD take turns on the matrix pipe one phase at a time: the wave that
-      // is behind (counted from the barrier) has the higher issue priority.
-      if (ph == 0) __builtin_amdgcn_s_setprio(2);
-      else if (ph == 1) __builtin_amdgcn_s_setprio(1);
-      else if (ph == 2) __builtin_amdgcn_s_setprio(0);
-      if (ph == 3) {
-        // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
-        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        __builtin_amdgcn_s_setprio(3);
+      for (int ph = 0; ph < 4; ++ph) {
+        const int kk = ph >> 1, h = ph & 1;
+        // The two waves of a SIMD take turns on the matrix pipe one phase at a time: the wave that
+        // is behind (counted from the barrier) has the higher issue priority.
+        if (ph == 0) __builtin_amdgcn_s_setprio(2);
+        else if (ph == 1) __builtin_amdgcn_s_setprio(1);
+        else if (ph == 2) __builtin_amdgcn_s_setprio(0);
+        if (ph == 3) {
+          // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
+          wait_dma_and_barrier<NIB>();
+          __builtin_amdgcn_s_setprio(3);
+          __builtin_amdgcn_sched_barrier(0);
+          read_a(aring + a_nxt, 0, 0);
+          read_b(bring + b_nxt, 0);
+        } else if (h == 0) {
+          read_a(aring + a_cur, kk, 1);
+        } else {
+          read_a(aring + a_cur, kk + 1, 0);
+          read_b(bring + b_cur, kk + 1);
+        }
+        if (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NIA / 2, NIA);
+        else if (ph < 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (ph - 1) * (NIB / 2), ph * (NIB / 2));
+        else issue(a_at(slab_k(it + 2)), a_off, aring + a_cur, 0, NIA / 2);
+        mfma_phase(kk, h);
+        if (h == 0) stream_sched<HM * TN, RA, NIA / 2>();
+        else stream_sched<HM * TN, RA + RB, NIA / 2>();
         __builtin_amdgcn_sched_barrier(0);
-        read_a(aring + a_nxt, 0, 0);
-        read_b(bring + b_nxt, 0);
-      } else if (h == 0) {
-        read_a(aring + a_cur, kk, 1);
-      } else {
-        read_a(aring + a_cur, kk + 1, 0);
-        read_b(bring + b_cur, kk + 1);
       }
-      if (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NI / 2, NI);
-      else if (ph < 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (ph - 1) * (NI / 2), ph * (NI / 2));
-      else issue(a_at(slab_k(it + 2)), a_off, aring + a_cur, 0, NI / 2);
-      mfma_phase(kk, h);
-      if (h == 0) stream_sched<HM * TN, RA, NI / 2>();
-      else stream_sched<HM * TN, RA + RB, NI / 2>();
-      __builtin_amdgcn_sched_barrier(0);
+      a_cur = a_nxt;
+      b_cur = b_nxt;
     }
-    a_cur = a_nxt;
-    b_cur = b_nxt;
+  } else {
+    // Two stages each way: the stages of slab `it` are free from the barrier of slab `it` on (every wave has
+    // read its last fragments of it), and slab it+2 goes there in three groups: all of B right after that
+    // barrier (phase 3), A in phases 0 and 1 of slab it+1; slab it+1 has to be complete at the barrier of
+    // slab it+1, when nothing else is in flight.
+    constexpr int A_FIRST = (NIA + 1) / 2;
+    issue(a_at(slab_k(0)), a_off, aring, 0, NIA);
+    issue(b_at(slab_k(0)), b_off, bring, 0, NIB);
+    issue(b_at(slab_k(1)), b_off, bring + B_STAGE, 0, NIB);
+    wait_dma_and_barrier<NIB>();   // A 0, B 0 landed
+    read_a(aring, 0, 0);
+    read_b(bring, 0);
+    for (int it = 0; it < nk; ++it) {
+      const int a_nxt = a_cur ^ A_STAGE, b_nxt = b_cur ^ B_STAGE;
+      auto phase = [&](auto PH) {
+        constexpr int ph = decltype(PH)::value, kk = ph >> 1, h = ph & 1;
+        constexpr int ndma = ph == 0 ? A_FIRST : ph == 1 ? NIA - A_FIRST : ph == 3 ? NIB : 0;
+        if constexpr (ph < 3) __builtin_amdgcn_s_setprio(2 - ph);
+        if constexpr (ph == 3) {
+          wait_dma_and_barrier<0>();   // slab it+1 complete
+          __builtin_amdgcn_s_setprio(3);
+          __builtin_amdgcn_sched_barrier(0);
+          read_a(aring + a_nxt, 0, 0);
+          read_b(bring + b_nxt, 0);
+        } else if constexpr (h == 0) {
+          read_a(aring + a_cur, kk, 1);
+        } else {
+          read_a(aring + a_cur, kk + 1, 0);
+          read_b(bring + b_cur, kk + 1);
+        }
+        if constexpr (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, 0, A_FIRST);
+        else if constexpr (ph == 1) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, A_FIRST, NIA);
+        else if constexpr (ph == 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_cur, 0, NIB);
+        mfma_phase(kk, h);
+        stream_sched<HM * TN, h == 0 ? RA : RA + RB, ndma>();
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      phase(std::integral_constant<int, 0>{});
+      phase(std::integral_constant<int, 1>{});
+      phase(std::integral_constant<int, 2>{});
+      phase(std::integral_constant<int, 3>{});
+      a_cur = a_nxt;
+      b_cur = b_nxt;
+    }
   }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   __builtin_amdgcn_s_setprio(0);
@@ -612,69 +696,85 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   // Epilogue, wave by wave with no workgroup barrier.  The MFMAs took the B fragment as their first
   // operand, so block (i, j) of the wave tile sits transposed in the registers: lane l holds row
   // 16 i + l % 16 and the four consecutive columns 16 j + 4 (l / 16) .. + 3.  Each wave turns its
-  // 128 x 64 tile, 64 rows at a time, through a private 64 x 68-float LDS patch (16-byte stores,
-  // conflict-free at that pitch) into 8-column row segments, so that every global access is 16
-  // bytes of a row and a wave instruction covers whole 128-byte lines.
+  // WM x WN tile, RP rows at a time, through a private LDS patch (16-byte stores,
+  // conflict-free at its pitch) into 8-column row segments, so that every global access is 16
+  // bytes of a row and a wave instruction covers whole lines.
+  // The lane and wave numbers pass through an empty asm statement here: the epilogue's addresses then cannot be
+  // computed ahead of the main loop, where they would occupy registers the loop needs (the 320-column tile has
+  // 160 of 256 in accumulators).
+  int elane = lane, ewave = wave;
+  asm volatile("" : "+v"(elane), "+v"(ewave));
+  const int ewm = ewave / WGN, ewn = ewave % WGN;
+  constexpr int RP = WN == 80 ? 32 : 64;        // rows per pass
+  constexpr int SEG = WN / 8;                   // 8-column segments per row
+  constexpr int NRD = RP * SEG / 64;            // read instructions per pass
+  static_assert(WM % RP == 0 && (RP * SEG) % 64 == 0, "epilogue passes must tile the wave tile");
   if (PLAIN16 && part_id < 0) {
     // bf16 output with at most a bias: round before the transposition, which halves the LDS
     // traffic of the patch and leaves the second half of the epilogue a plain 16-byte copy.
-    // Patch = 64 rows x 128 B per wave, 16-byte unit u of row r at unit position u ^ ((r >> 1) & 7)
+    // Patch = RP rows per wave; 64 columns: 128 B per row, 16-byte unit u of row r at unit position
+    // u ^ ((r >> 1) & 7); 80 columns: 256 B per row (10 units used), unit u at u ^ (r & 15)
     // (8-byte block stores and 16-byte row reads both conflict-free).
-    char *patch = smem + wave * 8192;
-    const int g4 = lane >> 4;
+    constexpr int PROW = WN == 64 ? 128 : 256;
+    char *patch = smem + ewave * (RP * PROW);
+    auto unit_pos = [](int unit, int row) { return WN == 64 ? (unit ^ ((row >> 1) & 7)) : (unit ^ (row & 15)); };
+    static_assert(WN == 64 || WN == 80, "patch layouts exist for these wave tile widths");
+    const int g4 = elane >> 4;
     f32x4 bias4[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) bias4[j][e] = 0.0f;
       if (g.ea.flags & MTNLG_EPI_BIAS) {
-        const bf16x4 bv = *reinterpret_cast<const bf16x4 *>(static_cast<const bf16 *>(g.ea.bias) + n0 + wn * WN + j * 16 + 4 * g4);
+        const bf16x4 bv = *reinterpret_cast<const bf16x4 *>(static_cast<const bf16 *>(g.ea.bias) + n0 + ewn * WN + j * 16 + 4 * g4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) bias4[j][e] = (float)bv[e];
       }
     }
-    bf16 *cbase = static_cast<bf16 *>(g.C) + (m0 + wm * WM) * g.ldc + n0 + wn * WN;
+    bf16 *cbase = static_cast<bf16 *>(g.C) + (m0 + ewm * WM) * g.ldc + n0 + ewn * WN;
 #pragma unroll
-    for (int p = 0; p < TM / 4; ++p) {
+    for (int p = 0; p < WM / RP; ++p) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < RP / 16; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int row = (lane & 15) + i * 16, unit = 2 * j + (g4 >> 1);
+          const int row = (elane & 15) + i * 16, unit = 2 * j + (g4 >> 1);
           bf16x4 h;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = (bf16)(acc[p * 4 + i][j][e] + bias4[j][e]);
-          *reinterpret_cast<bf16x4 *>(patch + row * 128 + ((unit ^ ((row >> 1) & 7)) << 4) + (g4 & 1) * 8) = h;
+          for (int e = 0; e < 4; ++e) h[e] = (bf16)(acc[p * (RP / 16) + i][j][e] + bias4[j][e]);
+          *reinterpret_cast<bf16x4 *>(patch + row * PROW + (unit_pos(unit, row) << 4) + (g4 & 1) * 8) = h;
         }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int row = t * 8 + (lane >> 3), cv = lane & 7;   // 8 rows x 8 segments per instruction
-        const bf16x8 o = *reinterpret_cast<const bf16x8 *>(patch + row * 128 + ((cv ^ ((row >> 1) & 7)) << 4));
-        *reinterpret_cast<bf16x8 *>(cbase + (int64_t)(p * 64 + row) * g.ldc + cv * 8) = o;
+      for (int t = 0; t < NRD; ++t) {
+        const int q = t * 64 + elane, row = q / SEG, cv = q % SEG;
+        const bf16x8 o = *reinterpret_cast<const bf16x8 *>(patch + row * PROW + (unit_pos(cv, row) << 4));
+        *reinterpret_cast<bf16x8 *>(cbase + (int64_t)(p * RP + row) * g.ldc + cv * 8) = o;
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // patch is rewritten by the next pass
     }
   } else {
-    constexpr int PITCH = WN + 4;
-    float *patch = reinterpret_cast<float *>(smem) + wave * (64 * PITCH);
+    constexpr int PITCH = WN + 4;   // floats; 68 and 84 both leave 16-byte block stores of 16 rows conflict-free
+    float *patch = reinterpret_cast<float *>(smem) + ewave * (RP * PITCH);
+    // one pass; instantiated per pass number so that the accumulator blocks are always named at compile time
+    // (a pass loop this large is not unrolled on request, and a rolled one would index the registers dynamically)
+    auto pass = [&](auto P) {
+      constexpr int p = decltype(P)::value;
 #pragma unroll
-    for (int p = 0; p < TM / 4; ++p) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < RP / 16; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          *reinterpret_cast<f32x4 *>(patch + ((lane & 15) + i * 16) * PITCH + j * 16 + 4 * (lane >> 4)) = acc[p * 4 + i][j];
+          *reinterpret_cast<f32x4 *>(patch + ((elane & 15) + i * 16) * PITCH + j * 16 + 4 * (elane >> 4)) = acc[p * (RP / 16) + i][j];
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int row = t * 8 + (lane >> 3), cv = lane & 7;   // 8 rows x 8 segments per instruction
+      for (int t = 0; t < NRD; ++t) {
+        const int q = t * 64 + elane, row = q / SEG, cv = q % SEG;
         float v[8];
         const f32x4 lo = *reinterpret_cast<const f32x4 *>(patch + row * PITCH + cv * 8);
         const f32x4 hi = *reinterpret_cast<const f32x4 *>(patch + row * PITCH + cv * 8 + 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
-        const int trow = wm * WM + p * 64 + row, tcol = wn * WN + cv * 8;   // position in the 256 x 256 tile
+        const int trow = ewm * WM + p * RP + row, tcol = ewn * WN + cv * 8;   // position in the tile
         if (part_id >= 0) {  // K-part of a tail tile: raw fp32 partial, summed by splitk_reduce_kernel
           store8(g.partial + (int64_t)part_id * (BM * BN) + trow * BN + tcol, v);
         } else {
@@ -682,7 +782,15 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // patch is rewritten by the next pass
+    };
+    static_assert(WM / RP == 2 || WM / RP == 4 || WM / RP == 5, "passes are written out below");
+    pass(std::integral_constant<int, 0>{});
+    pass(std::integral_constant<int, 1>{});
+    if constexpr (WM / RP > 2) {
+      pass(std::integral_constant<int, 2>{});
+      pass(std::integral_constant<int, 3>{});
     }
+    if constexpr (WM / RP > 4) pass(std::integral_constant<int, 4>{});
   }
 }
 
@@ -734,22 +842,33 @@ inline SplitPlan plan_split(int64_t tiles, int nk, int bm, int bn, size_t ws_byt
   return p;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, bool KTAIL>
-int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
-  GemmArgs g = in;
+// Tile numbering, XCD slices and the split-K plan of one launch.
+template <int BM, int BN>
+int plan_launch(GemmArgs &g, void *ws, size_t ws_bytes, bool allow_split, unsigned *grid, SplitPlan *plan_out) {
   g.tiles_m = (int)((g.M + BM - 1) / BM);
   g.tiles_n = (int)((g.N + BN - 1) / BN);
   const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
   if (tiles > (1 << 28)) return MTNLG_UNSUPPORTED_SHAPE;
   const int nk = (int)((g.K + BK - 1) / BK);
-  const SplitPlan plan = plan_split(tiles, nk, BM, BN, ws ? ws_bytes : 0);
+  SplitPlan plan = plan_split(tiles, nk, BM, BN, (ws && allow_split) ? ws_bytes : 0);
   const bool split = plan.tail > 0;
   g.whole_tiles = split ? plan.whole : (int)tiles;
   g.split = split ? plan.split : 1;
   g.part_slabs = split ? plan.part_slabs : nk;
   g.partial = (float *)ws;
   g.per_xcd = (g.whole_tiles + 7) / 8;
-  const unsigned grid = (unsigned)(g.per_xcd * 8 + (split ? plan.tail * plan.split : 0));
+  *grid = (unsigned)(g.per_xcd * 8 + (split ? plan.tail * plan.split : 0));
+  *plan_out = plan;
+  return MTNLG_OK;
+}
+
+// General kernel: any shape within its alignment rules.
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT, bool KTAIL>
+int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
+  GemmArgs g = in;
+  unsigned grid;
+  SplitPlan plan;
+  MTNLG_TRY((plan_launch<BM, BN>(g, ws, ws_bytes, true, &grid, &plan)));
   constexpr int stages = 2 * (BM + BN) * BK * 2, image = (BM / WGM) * BN * 4;
   constexpr int smem = stages > image ? stages : image;
   static unsigned long long attr_done = 0;
@@ -760,35 +879,9 @@ int launch_k(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
       return MTNLG_HIP_ERROR;
     attr_mark_set(attr_done, device);
   }
-  // Aligned problems on the default tile shape take the streaming kernel (all operands by DMA).
-  if constexpr (BM == 256 && BN == 256 && WGM == 2 && WGN == 4 && !KTAIL) {
-    if (g.M % 256 == 0 && g.N % 256 == 0) {
-      constexpr int stream_smem = 5 * 256 * BK * 2;
-      static unsigned long long stream_attr_done = 0;
-      if (!attr_is_set(stream_attr_done, &device)) {
-        if (hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess ||
-            hipFuncSetAttribute((const void *)gemm_stream_kernel<AT, BT, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, stream_smem) != hipSuccess)
-          return MTNLG_HIP_ERROR;
-        attr_mark_set(stream_attr_done, device);
-      }
-      // bf16 output with nothing but an optional bias: the epilogue that rounds before it transposes
-      if ((g.ea.flags & ~(uint32_t)MTNLG_EPI_BIAS) == 0)
-        gemm_stream_kernel<AT, BT, true><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
-      else
-        gemm_stream_kernel<AT, BT, false><<<dim3(grid), 64 * WGM * WGN, stream_smem, st>>>(g);
-      MTNLG_TRY(check_launch());
-      if (split) {
-        splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
-        MTNLG_TRY(check_launch());
-      }
-      return MTNLG_OK;
-    }
-  }
   gemm_bf16_kernel<BM, BN, WGM, WGN, AT, BT, KTAIL><<<dim3(grid), 64 * WGM * WGN, smem, st>>>(g);
   MTNLG_TRY(check_launch());
-  if (split) {
+  if (plan.tail > 0) {
     splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
     MTNLG_TRY(check_launch());
   }
@@ -801,51 +894,108 @@ int launch(const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
                   : launch_k<BM, BN, WGM, WGN, AT, BT, false>(g, ws, ws_bytes, st);
 }
 
-// Tile shapes on offer: {BM, BN, waves_m, waves_n}
-enum TileConfig { T256x256_2x2 = 0, T128x128_2x2, T256x256_2x4, T256x128_2x2, T128x256_2x2, TILE_CONFIGS };
+// Streaming kernel: M a multiple of BM, N of BN, K of 64.  Only 256 x 256 tiles split a last round along K.
+template <int BM, int BN, bool AT, bool BT>
+int launch_stream(const GemmArgs &in, void *ws, size_t ws_bytes, hipStream_t st) {
+  GemmArgs g = in;
+  if (g.M % BM || g.N % BN || g.K % BK) return MTNLG_UNSUPPORTED_SHAPE;
+  unsigned grid;
+  SplitPlan plan;
+  MTNLG_TRY((plan_launch<BM, BN>(g, ws, ws_bytes, BM == 256 && BN == 256, &grid, &plan)));
+  constexpr int ring_b = (BM == 256 && BN == 256) ? 3 : 2;
+  constexpr int smem = (2 * BM + ring_b * BN) * BK * 2;
+  static unsigned long long attr_done = 0;
+  int device;
+  if (!attr_is_set(attr_done, &device)) {
+    if (hipFuncSetAttribute((const void *)gemm_stream_kernel<BM, BN, AT, BT, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess ||
+        hipFuncSetAttribute((const void *)gemm_stream_kernel<BM, BN, AT, BT, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return MTNLG_HIP_ERROR;
+    attr_mark_set(attr_done, device);
+  }
+  // bf16 output with nothing but an optional bias: the epilogue that rounds before it transposes
+  if ((g.ea.flags & ~(uint32_t)MTNLG_EPI_BIAS) == 0)
+    gemm_stream_kernel<BM, BN, AT, BT, true><<<dim3(grid), 512, smem, st>>>(g);
+  else
+    gemm_stream_kernel<BM, BN, AT, BT, false><<<dim3(grid), 512, smem, st>>>(g);
+  MTNLG_TRY(check_launch());
+  if (plan.tail > 0) {
+    splitk_reduce_kernel<BM, BN><<<dim3(8, plan.tail), 256, 0, st>>>(g);
+    MTNLG_TRY(check_launch());
+  }
+  return MTNLG_OK;
+}
 
 template <bool AT, bool BT>
-int launch_config(int cfg, const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
-  switch (cfg) {
-    case T256x256_2x2: return launch<256, 256, 2, 2, AT, BT>(g, ws, ws_bytes, st);
-    case T128x128_2x2: return launch<128, 128, 2, 2, AT, BT>(g, ws, ws_bytes, st);
-    case T256x256_2x4: return launch<256, 256, 2, 4, AT, BT>(g, ws, ws_bytes, st);
-    case T256x128_2x2: return launch<256, 128, 2, 2, AT, BT>(g, ws, ws_bytes, st);
-    case T128x256_2x2: return launch<128, 256, 2, 2, AT, BT>(g, ws, ws_bytes, st);
+int launch_tile(int tile, const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
+  switch (tile) {
+    case GEMM_TILE_GENERAL_256: return launch<256, 256, 2, 4, AT, BT>(g, ws, ws_bytes, st);
+    case GEMM_TILE_GENERAL_128: return launch<128, 128, 2, 2, AT, BT>(g, ws, ws_bytes, st);
+    case GEMM_TILE_STREAM_256x256: return launch_stream<256, 256, AT, BT>(g, ws, ws_bytes, st);
+    case GEMM_TILE_STREAM_256x320: return launch_stream<256, 320, AT, BT>(g, ws, ws_bytes, st);
     default: return MTNLG_INVALID_ARG;
   }
 }
 
-template <bool AT, bool BT>
-int pick_tile(const GemmArgs &g, void *ws, size_t ws_bytes, hipStream_t st) {
-  // 256x256 tiles on 8 waves measure fastest per tile.  A last round that would leave
-  // most CUs idle is split along K instead (needs workspace); without workspace, problems
-  // too small to give most CUs one big tile take 128x128 tiles (two workgroups per CU).
-  const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  const int nk = (int)((g.K + BK - 1) / BK);
-  const SplitPlan plan = plan_split(tiles256, nk, 256, 256, ws ? ws_bytes : 0);
-  if (plan.tail == 0 && tiles256 < 160) return launch_config<AT, BT>(T128x128_2x2, g, ws, ws_bytes, st);
-  return launch_config<AT, BT>(T256x256_2x4, g, ws, ws_bytes, st);
+// Rounds of 256 workgroups a tiling needs, counting a last round that is split along K by its share.
+double rounds_of(int64_t tiles, bool can_split, int nk) {
+  const int cus = 256;
+  if (can_split && plan_split(tiles, nk, 256, 256, ~(size_t)0).tail > 0) return (double)tiles / cus + 0.15;
+  return (double)((tiles + cus - 1) / cus);
 }
 
 }  // namespace
 
-size_t gemm_mfma_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+// Which kernel and tile shape take a problem.  Aligned problems go to the streaming kernel; among its tile
+// shapes the one with the least estimated time wins: rounds of 256 tiles x tile area x a measured relative
+// cost per FLOP of the shape (wider tiles move fewer operand bytes per FLOP).  Without workspace a last
+// round cannot be split along K and counts in full.
+int gemm_mfma_pick_tile(int layout, int64_t M, int64_t N, int64_t K, bool have_workspace) {
+  if (M <= 0 || N <= 0 || K <= 0) return GEMM_TILE_GENERAL_256;
+  const int nk = (int)((K + BK - 1) / BK);
+  if (K % BK == 0 && M % 256 == 0) {
+    double best = 1e300;
+    int pick = -1;
+    auto offer = [&](int tile, int64_t bm, int64_t bn, double cost_per_flop, bool can_split) {
+      if (M % bm || N % bn) return;
+      const int64_t tiles = (M / bm) * (N / bn);
+      const double t = rounds_of(tiles, can_split && have_workspace, nk) * (double)(bm * bn) * cost_per_flop;
+      if (t < best) { best = t; pick = tile; }
+    };
+    const int64_t tiles256 = N % 256 == 0 ? (M / 256) * (N / 256) : 0;
+    // small problems: 128 x 128 tiles of the general kernel (two workgroups per compute unit)
+    const bool small = tiles256 > 0 && tiles256 < 160 && !(have_workspace && plan_split(tiles256, nk, 256, 256, ~(size_t)0).tail > 0);
+    if (!small || N % 256) {
+      offer(GEMM_TILE_STREAM_256x256, 256, 256, 1.00, true);
+      // the wider tile does not fit the registers of the weight-gradient form (both operands through transposing
+      // reads: 13 address registers on top of 160 accumulators and 72 fragment registers)
+      if (layout != MTNLG_GEMM_TN) offer(GEMM_TILE_STREAM_256x320, 256, 320, GEMM_COST_256x320, false);
+      if (pick >= 0) return pick;
+    }
+  }
+  const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+  const SplitPlan plan = plan_split(tiles256, nk, 256, 256, have_workspace ? ~(size_t)0 : 0);
+  if (plan.tail == 0 && tiles256 < 160) return GEMM_TILE_GENERAL_128;
+  return GEMM_TILE_GENERAL_256;
+}
+
+size_t gemm_mfma_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K) {
   if (M <= 0 || N <= 0 || K <= 0) return 0;
+  const int tile = gemm_mfma_pick_tile(layout, M, N, K, true);
+  if (tile != GEMM_TILE_STREAM_256x256 && tile != GEMM_TILE_GENERAL_256) return 0;
   const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
   return plan_split(tiles256, (int)((K + BK - 1) / BK), 256, 256, 0).workspace;
 }
 
-bool gemm_mfma_streams(int64_t M, int64_t N, int64_t K) {
-  if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % BK) return false;
-  // same choice as pick_tile: small problems take 128x128 tiles
-  const int64_t tiles256 = (M / 256) * (N / 256);
-  return tiles256 >= 160 || plan_split(tiles256, (int)(K / BK), 256, 256, ~(size_t)0).tail > 0;
+bool gemm_mfma_streams(int layout, int64_t M, int64_t N, int64_t K) {
+  const int tile = gemm_mfma_pick_tile(layout, M, N, K, true);
+  return tile == GEMM_TILE_STREAM_256x256 || tile == GEMM_TILE_STREAM_256x320;
 }
 
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
                    const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes, hipStream_t stream,
-                   int prof_class) {
+                   int prof_class, int tile) {
   if (K % 8 || N % 8) return MTNLG_UNSUPPORTED_SHAPE;
   const bool at = layout == MTNLG_GEMM_TN, bt = layout != MTNLG_GEMM_NT;
   if ((at && (M % 8 || M < 8)) || (bt && (N % 8 || N < 8))) return MTNLG_UNSUPPORTED_SHAPE;
@@ -858,10 +1008,12 @@ int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, c
   g.ea = EpiArgs{bias, aux, epi};
   g.tiles_m = g.tiles_n = g.per_xcd = 0;
   g.whole_tiles = 0; g.split = 1; g.part_slabs = 0; g.partial = nullptr;
+  if (tile < 0)
+    tile = gemm_mfma_pick_tile(layout, M, N, K, ws != nullptr && ws_bytes >= gemm_mfma_workspace_bytes(layout, M, N, K));
   LaunchScope scope(prof_class >= 0 ? prof_class : MTNLG_K_GEMM_NT + layout, stream);
-  if (!at && !bt) return pick_tile<false, false>(g, ws, ws_bytes, stream);
-  if (!at && bt) return pick_tile<false, true>(g, ws, ws_bytes, stream);
-  return pick_tile<true, true>(g, ws, ws_bytes, stream);
+  if (!at && !bt) return launch_tile<false, false>(tile, g, ws, ws_bytes, stream);
+  if (!at && bt) return launch_tile<false, true>(tile, g, ws, ws_bytes, stream);
+  return launch_tile<true, true>(tile, g, ws, ws_bytes, stream);
 }
 
 }  // namespace mtnlg

@@ -58,18 +58,20 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
     A = torch.randn(a_shape, generator=g, device="cuda").bfloat16()
     Bm = (torch.randn(b_shape, generator=g, device="cuda") * 0.05).bfloat16()
     bias = torch.randn((N,), generator=g, device="cuda").bfloat16() if epi & B.EPI_BIAS else None
-    aux = torch.randn((Mm, N), generator=g, device="cuda").bfloat16() if epi & (B.EPI_RESIDUAL | B.EPI_GELU) else None
+    aux = (torch.randn((Mm, N), generator=g, device="cuda").bfloat16()
+           if epi & (B.EPI_RESIDUAL | B.EPI_GELU | B.EPI_GELU_GRAD) else None)
     if epi & B.EPI_ACCUMULATE:  # the micro-batch loop's weight-gradient form: fp32 buffer, added to
         C = torch.randn((Mm, N), generator=g, device="cuda", dtype=torch.float32 if epi & B.EPI_OUT_F32 else torch.bfloat16)
         before = C.clone()
     else:
         C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    res = aux.clone() if epi & B.EPI_RESIDUAL else None
+    res = aux.clone() if epi & (B.EPI_RESIDUAL | B.EPI_GELU_GRAD) else None
     need = M.mtnlg_gemm_workspace(B.BF16, layout, Mm, N, K)
     ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
     M.mtnlg_gemm(layout, A, Bm, C, bias=bias, aux=aux, epilogue=epi, workspace=ws)
+    # first / interior / last tiles, and both sides of the 64-, 80-, 256- and 320-column seams of the tile shapes
     rows = sorted({r for r in (0, 1, 127, 128, 255, 256, Mm // 2 + 3, Mm - 129, Mm - 1)})
-    cols = sorted({c for c in (0, 7, 255, 256, N // 2 + 5, N - 257, N - 1)})
+    cols = sorted({c for c in (0, 7, 63, 64, 79, 80, 255, 256, 319, 320, 639, 640, N // 2 + 5, N - 321, N - 257, N - 1)})
     # operand rows / columns of the samples are picked on the device: the whole operands need not cross to the host
     if layout == B.GEMM_NT:
         want = oracle.linear_fwd(to_np(A[rows]), to_np(Bm[cols]), to_np(bias)[cols] if bias is not None else None)
@@ -82,6 +84,8 @@ def _gemm_case(layout, Mm, N, K, epi=0, seed=0):
         want = oracle.gelu(want)
     if epi & B.EPI_RESIDUAL:
         want = want + to_np(res)[np.ix_(rows, cols)]
+    if epi & B.EPI_GELU_GRAD:
+        want = want * oracle.gelu_grad(to_np(res)[np.ix_(rows, cols)])
     if epi & B.EPI_ACCUMULATE:
         want = want + to_np(before)[np.ix_(rows, cols)]
     assert_close(C[rows][:, cols], want, TOL["bf16"], f"gemm {layout} {Mm}x{N}x{K} samples")
@@ -92,7 +96,7 @@ T, H, P, F = WL.tokens, WL.hidden, WL.proj, WL.ffn
 FULL_GEMMS = [
     ("qkv", B.GEMM_NT, T, 3 * P, H, B.EPI_BIAS), ("proj", B.GEMM_NT, T, H, P, B.EPI_BIAS | B.EPI_RESIDUAL),
     ("fc1", B.GEMM_NT, T, F, H, B.EPI_BIAS | B.EPI_GELU), ("fc2", B.GEMM_NT, T, H, F, B.EPI_BIAS | B.EPI_RESIDUAL),
-    ("dfc2", B.GEMM_NN, T, F, H, 0), ("dfc1", B.GEMM_NN, T, H, F, 0), ("dproj", B.GEMM_NN, T, P, H, 0),
+    ("dfc2", B.GEMM_NN, T, F, H, 0), ("dfc2_gelu_grad", B.GEMM_NN, T, F, H, B.EPI_GELU_GRAD), ("dfc1", B.GEMM_NN, T, H, F, 0), ("dproj", B.GEMM_NN, T, P, H, 0),
     ("dqkv", B.GEMM_NN, T, H, 3 * P, 0),
     ("wfc2", B.GEMM_TN, H, F, T, 0), ("wfc1", B.GEMM_TN, F, H, T, 0), ("wproj", B.GEMM_TN, H, P, T, 0),
     ("wqkv", B.GEMM_TN, 3 * P, H, T, 0),

@@ -91,6 +91,15 @@ def test_gemm_epilogues(dtype, shape):
                      epilogue=B.EPI_BIAS | B.EPI_GELU | (B.EPI_GELU_ERF if erf_form else 0))
         assert_close(Z, want, tol, "pre-activation")
         assert_close(C, oracle.gelu(want, exact=erf_form), tol, f"gelu erf={erf_form}")
+    # the activation's backward fused into the product: C = (A W^T) o GeLU'(aux), both forms, aux untouched
+    for erf_form in (False, True):
+        Z = dres.clone()
+        M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, aux=Z, epilogue=B.EPI_GELU_GRAD | (B.EPI_GELU_ERF if erf_form else 0))
+        assert torch.equal(Z, dres)
+        assert_close(C, gemm_oracle(B.GEMM_NT, A, W) * oracle.gelu_grad(to_np(res), exact=erf_form), tol,
+                     f"gelu grad erf={erf_form}")
+    with pytest.raises(B.MtnlgError):
+        M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, bias=dbias, aux=dres, epilogue=B.EPI_GELU_GRAD | B.EPI_BIAS)
     # bias + residual
     M.mtnlg_gemm(B.GEMM_NT, dA, dW, C, bias=dbias, aux=dres, epilogue=B.EPI_BIAS | B.EPI_RESIDUAL)
     assert_close(C, want + to_np(res), tol, "bias+residual")

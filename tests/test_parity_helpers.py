@@ -45,6 +45,23 @@ def test_local_damage_below_the_norm_bar_is_caught(want, damage):
         assert_close(got, want, TOL["bf16"], damage)
 
 
+def test_rows_of_very_different_size():
+    """A weight-gradient-like matrix (outer-product structure: row i scaled by a_i, column j by b_j, scales over an
+    order of magnitude): errors proportional to the local size pass, damage in a small-valued region is still seen."""
+    rng = np.random.default_rng(3)
+    a = np.exp(rng.uniform(-1.5, 1.5, (1024, 1)))
+    b = np.exp(rng.uniform(-1.0, 1.0, (1, 2048)))
+    want = a * b * rng.standard_normal((1024, 2048))
+    got = want + 4e-3 * a * b * rng.standard_normal(want.shape)
+    assert_close(got, want, TOL["bf16"], "noise proportional to row and column size")
+    small_rows = np.argsort(a[:, 0])[:16]
+    got2 = bf16_round(want)
+    got2[small_rows[:, None], np.arange(64, 80)[None, :]] = 0.0     # a 16 x 16 hole where values are smallest
+    assert rel_fro(got2, want) < TOL["bf16"]
+    with pytest.raises(AssertionError, match="allowance"):
+        assert_close(got2, want, TOL["bf16"], "hole in the smallest rows")
+
+
 def test_fp32_bar_and_degenerate_inputs():
     rng = np.random.default_rng(2)
     w = rng.standard_normal((300, 300))
