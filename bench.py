@@ -52,9 +52,12 @@ def measured_peaks(x, reps=5):
         return e0.elapsed_time(e1) / reps
 
     ms_mfma = timed(lambda: M.mtnlg_calibrate_mfma(wgs, iters, ops, out))
+    zeros = torch.zeros_like(ops)   # the same loop on zeros: what the matrix pipes do when the data toggles nothing
+    ms_zero = timed(lambda: M.mtnlg_calibrate_mfma(wgs, iters, zeros, out))
     ms_copy = timed(lambda: M.mtnlg_calibrate_copy(dst, src))
     fl = M.mtnlg_calibrate_mfma_flops(wgs, iters)
     return {"mfma_tflops": fl / (ms_mfma * 1e-3) / 1e12, "mfma_ms": ms_mfma,
+            "mfma_tflops_zeros": fl / (ms_zero * 1e-3) / 1e12,
             "copy_gbps": 2 * (1 << 30) / (ms_copy * 1e-3) / 1e9, "copy_ms": ms_copy}
 
 
@@ -164,9 +167,9 @@ def optimizer_step_bench(weights, reps=3):
             "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "bound": "hbm"}
 
 
-# kernel symbol of each GEMM class in the rocprofv3 summaries (template arguments: A transposed, B transposed)
-CLASS_SYMBOL = {"gemm_nt": "gemm_stream_kernel<false, false", "gemm_nn": "gemm_stream_kernel<false, true",
-                "gemm_tn": "gemm_stream_kernel<true, true"}
+# kernel symbol of each GEMM class in the rocprofv3 summaries: gemm_stream_kernel<BM, BN, A transposed, B transposed, ...>
+CLASS_SYMBOL = {"gemm_nt": r"gemm_stream_kernel<\d+, \d+, false, false", "gemm_nn": r"gemm_stream_kernel<\d+, \d+, false, true",
+                "gemm_tn": r"gemm_stream_kernel<\d+, \d+, true, true"}
 
 
 def counter_traffic(cls):
@@ -179,7 +182,8 @@ def counter_traffic(cls):
         table = json.loads(line[len("TRAFFIC_TABLE "):])
     except (OSError, IndexError, ValueError):
         return None
-    rows = [v for k, v in table.items() if k.startswith(CLASS_SYMBOL[cls])]
+    import re
+    rows = [v for k, v in table.items() if re.match(CLASS_SYMBOL[cls], k)]
     n = sum(r["launches"] for r in rows)
     return int(sum(r["launches"] * r["bytes_per_launch"] for r in rows) / n) if n else None
 
@@ -194,8 +198,8 @@ def main():
     ap.add_argument("--cpu-prefix", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
-                    help="before the timed steps, run one plain device copy of BYTES (a known-size kernel to "
-                         "calibrate FETCH_SIZE / WRITE_SIZE counters against)")
+                    help="before the timed steps, run one plain streaming copy of BYTES (mtnlg_calibrate_copy: a kernel "
+                         "of known size to calibrate FETCH_SIZE / WRITE_SIZE counters against)")
     ap.add_argument("--micro-batches", type=int, default=1, metavar="K",
                     help="a step = K micro-batches through mtnlg_stage_step_accumulate with fp32 gradient buffers "
                          "(gradient accumulation); default 1 = the plain step the metric is quoted on")
@@ -253,7 +257,7 @@ def main():
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        M.mtnlg_calibrate_copy(dst, src)   # calibrate_copy_kernel in the profiler's listing
         torch.cuda.synchronize()
         del src, dst
     if not args.no_kernel_timing:
@@ -314,6 +318,7 @@ def main():
         if peaks is not None:
             # the same fractions against what a loop of nothing but matrix-core instructions sustains here
             out["roofline"]["measured_peak"] = round(peaks["mfma_tflops"], 1)
+            out["roofline"]["measured_peak_zero_operands"] = round(peaks["mfma_tflops_zeros"], 1)
             out["roofline"]["frac_of_measured"] = round(ach / peaks["mfma_tflops"], 4)
             out["pct_of_measured_mfma_loop"] = round(100 * value / peaks["mfma_tflops"], 2)
         # bandwidth-bound classes: achieved GB/s on their algorithmic bytes against the HBM peak
