@@ -147,7 +147,10 @@ size_t mtnlg_workspace_bytes(const mtnlg_layer_desc *desc);
 
 /* --- the hot path ------------------------------------------------------------ */
 
-/* Forward of one layer slice (equations at the top of this file).
+/* Forward of one layer slice: the decoder layer of the paper's Section 3.2 ("Model and Training Process") under the
+ * tensor slicing of Section 2.1 ("Tensor Model Parallelism"): column-parallel QKV and FC1, row-parallel projection
+ * and FC2 whose outputs are partial sums; storage in bf16 with fp32 arithmetic as in Section 2.3 (equations at the
+ * top of this file).
  *   x [T,h] in, y [T,h] out (y must not alias x); saved: this layer's block of
  *   mtnlg_saved_bytes() bytes, written; workspace: scratch, contents destroyed.
  *   reduce/user: tensor-parallel sum hook or NULL.  stream: hipStream_t (NULL =
@@ -156,7 +159,10 @@ int mtnlg_layer_fwd(const mtnlg_layer_desc *desc, const mtnlg_layer_weights *w, 
                     void *y, void *saved, void *workspace, size_t workspace_bytes,
                     mtnlg_reduce_fn reduce, void *user, void *stream);
 
-/* Backward of one layer slice: the adjoint of mtnlg_layer_fwd.
+/* Backward of one layer slice: the adjoint of mtnlg_layer_fwd, i.e. the other half of the per-GPU work that the
+ * paper's Section 2.4 throughput figures count; the two backward sums over the tensor-parallel group of Section 2.1
+ * sit at the hook.  Parameter gradients in the storage type ("2 bytes" per gradient, Section 2.1 "Memory
+ * Efficiency") or in float under MTNLG_WGRAD_FP32 (the fp32 gradient copy of the same passage).
  *   x: the layer input given to forward; saved: the block forward wrote;
  *   dy [T,h]: gradient of y; dx [T,h] out: gradient of x (may not alias dy);
  *   grads: all 12 parameter gradients, overwritten, or added to under
@@ -166,7 +172,10 @@ int mtnlg_layer_bwd(const mtnlg_layer_desc *desc, const mtnlg_layer_weights *w, 
                     void *workspace, size_t workspace_bytes, mtnlg_reduce_fn reduce, void *user,
                     void *stream);
 
-/* One pipeline-stage step: forward through n_layers stacked slices (layer l's y
+/* One pipeline-stage step -- what one GPU of a pipeline stage does for one micro-batch (Section 2.1, paragraph
+ * "Pipeline Model Parallelism"; Section 3.2: 105 layers under 35-way pipeline parallelism = 3 layers per GPU;
+ * Section 2.1, paragraph "Memory Efficiency", for the activation recomputation that MTNLG_RECOMPUTE selects):
+ * forward through n_layers stacked slices (layer l's y
  * is layer l+1's x), then backward through them in reverse, all on `stream`
  * with no host synchronisation.  w and grads are host arrays of n_layers tables.
  *   x_in [T,h], dy_out [T,h] in; y_out [T,h], dx_in [T,h] out.
@@ -180,8 +189,9 @@ int mtnlg_stage_step(const mtnlg_layer_desc *desc, int n_layers, const mtnlg_lay
                      void *stream);
 
 /* The same step over n_micro micro-batches with the parameter gradients summed over them -- the
- * gradient accumulation of Section 2.1 (memory-efficient training) as one pipeline rank sees it in the
- * steady state of the 1F1B schedule of Section 2.2: micro-batch 0 overwrites the gradient buffers
+ * gradient accumulation of Section 2.1 (paragraph "Memory Efficiency") as one pipeline rank sees it in the
+ * steady state of the 1F1B schedule (Section 2.1, paragraph "Pipeline Model Parallelism"): micro-batch 0 overwrites
+ * the gradient buffers
  * (adds to them if desc carries MTNLG_ACCUMULATE_WGRAD), the following ones add.  With bf16 gradient
  * buffers every addition rounds; MTNLG_WGRAD_FP32 gives the fp32 buffers the paper accumulates in.
  *   x_in, dy_out in, y_out, dx_in out: [n_micro][T,h], micro-batches contiguous one after the other.
