@@ -213,6 +213,9 @@ def main():
                     help="skip the matrix-core-only loop and the 1 GiB copy that measure what the chip sustains")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event bracketing of kernels (roofline.achieved becomes null)")
+    ap.add_argument("--kernel-timing-every", type=int, default=4, metavar="N",
+                    help="bracket the kernels of every N-th timed step with HIP events (the events cost 0.6 %% of a "
+                         "step); 1 = every step")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1", file=sys.stderr)
@@ -260,8 +263,11 @@ def main():
         M.mtnlg_calibrate_copy(dst, src)   # calibrate_copy_kernel in the profiler's listing
         torch.cuda.synchronize()
         del src, dst
+    every = max(1, args.kernel_timing_every)
+    sampled = [i for i in range(args.steps) if i % every == 0]
     if not args.no_kernel_timing:
         M.mtnlg_profile_enable(True)
+        M.mtnlg_profile_pause(True)
     # one event after every step (on the stream the steps run on) gives the spread over the steps; the
     # headline time stays the wall clock around all of them
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
@@ -269,7 +275,12 @@ def main():
     t0 = time.perf_counter()
     marks[0].record()
     for i in range(args.steps):
+        timed_kernels = not args.no_kernel_timing and i % every == 0
+        if timed_kernels:
+            M.mtnlg_profile_pause(False)
         one_step()
+        if timed_kernels:
+            M.mtnlg_profile_pause(True)
         marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -298,15 +309,16 @@ def main():
     }
     if prof is not None:
         gf = {k: v * args.micro_batches for k, v in gemm_flops_per_step(wl).items()}
+        nsamp = len(sampled)   # steps whose kernels were bracketed
         classes = {}
         for k, (n, tms) in prof.items():
             if n:
-                classes[k] = {"launches_per_step": n / args.steps, "ms_per_step": round(tms / args.steps, 4)}
+                classes[k] = {"launches_per_step": n / nsamp, "ms_per_step": round(tms / nsamp, 4)}
         dom = max(("gemm_nt", "gemm_nn", "gemm_tn"), key=lambda k: prof[k][1])
-        g_ms = sum(prof[k][1] for k in gf) / args.steps
+        g_ms = sum(prof[k][1] for k in gf) / nsamp
         for k in gf:
-            classes[k]["tflops"] = round(gf[k] / (prof[k][1] / args.steps * 1e-3) / 1e12, 1)
-        ach = gf[dom] / (prof[dom][1] / args.steps * 1e-3) / 1e12
+            classes[k]["tflops"] = round(gf[k] / (prof[k][1] / nsamp * 1e-3) / 1e12, 1)
+        ach = gf[dom] / (prof[dom][1] / nsamp * 1e-3) / 1e12
         # the counter summary was taken on the default workload only
         traffic = counter_traffic(dom) if wl.name == "mtnlg_tp8_stage" and args.micro_batches == 1 else None
         out["roofline"] = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS,
@@ -314,7 +326,8 @@ def main():
                            "traffic_source": "profiles/stage_step_mtnlg_tp8_hbm_traffic.txt (two rocprofv3 --pmc runs "
                                              "of this command; counters cannot be read inside the timed run)",
                            "all_gemm_tflops": round(sum(gf.values()) / (g_ms * 1e-3) / 1e12, 1),
-                           "gemm_share_of_step": round(g_ms / ms, 3)}
+                           "gemm_share_of_step": round(g_ms / ms, 3),
+                           "kernel_timed_steps": nsamp}
         if peaks is not None:
             # the same fractions against what a loop of nothing but matrix-core instructions sustains here
             out["roofline"]["measured_peak"] = round(peaks["mfma_tflops"], 1)

@@ -375,6 +375,8 @@ enum mtnlg_kernel_class {
   MTNLG_K_CLASSES
 };
 int mtnlg_profile_enable(int on);
+/* paused != 0: stop recording, keep what is recorded; 0: record again (timing must have been enabled). */
+int mtnlg_profile_pause(int paused);
 int mtnlg_profile_read(int32_t *launches /*[MTNLG_K_CLASSES]*/, float *ms /*[MTNLG_K_CLASSES]*/);
 
 /* --- measurement aids: what the chip sustains, with the benchmark's data, on the two resources that

@@ -125,6 +125,7 @@ def lib():
             "mtnlg_calibrate_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, vp, vp]),
             "mtnlg_calibrate_copy": (ctypes.c_int, [vp, vp, i64, vp]),
             "mtnlg_profile_enable": (ctypes.c_int, [ctypes.c_int]),
+            "mtnlg_profile_pause": (ctypes.c_int, [ctypes.c_int]),
             "mtnlg_profile_read": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]),
         }
         for name, (res, args) in sigs.items():
@@ -143,7 +144,7 @@ EXPORTED = ("mtnlg_version", "mtnlg_status_string", "mtnlg_layer_desc_check", "m
             "mtnlg_bias_residual", "mtnlg_grad_sqnorm_workspace", "mtnlg_grad_sqnorm", "mtnlg_adam_step",
             "mtnlg_lm_head_workspace", "mtnlg_embedding_fwd", "mtnlg_embedding_bwd", "mtnlg_lm_head_step",
             "mtnlg_calibrate_mfma_operand_bytes", "mtnlg_calibrate_mfma_flops", "mtnlg_calibrate_mfma",
-            "mtnlg_calibrate_copy", "mtnlg_profile_enable", "mtnlg_profile_read")
+            "mtnlg_calibrate_copy", "mtnlg_profile_enable", "mtnlg_profile_pause", "mtnlg_profile_read")
 
 
 def status_string(status):
@@ -469,6 +470,10 @@ def mtnlg_calibrate_copy(dst, src):
 
 def mtnlg_profile_enable(on):
     _check(lib().mtnlg_profile_enable(int(bool(on))), "mtnlg_profile_enable")
+
+
+def mtnlg_profile_pause(paused):
+    _check(lib().mtnlg_profile_pause(int(bool(paused))), "mtnlg_profile_pause")
 
 
 def mtnlg_profile_read():

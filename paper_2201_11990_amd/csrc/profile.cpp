@@ -79,6 +79,14 @@ extern "C" int mtnlg_profile_enable(int on) {
   return MTNLG_OK;
 }
 
+// Stop (paused != 0) or resume recording without touching what has been recorded: lets a caller bracket some of
+// its steps and leave the others free of events.
+extern "C" int mtnlg_profile_pause(int paused) {
+  g_enabled = !paused;
+  g_chain_end = nullptr;   // the next scope records a beginning of its own
+  return MTNLG_OK;
+}
+
 extern "C" int mtnlg_profile_read(int32_t *launches, float *ms) {
   if (!launches || !ms) return MTNLG_NULL_POINTER;
   for (int i = 0; i < MTNLG_K_CLASSES; ++i) {
