@@ -46,6 +46,33 @@ def test_gemm_plain(dtype, layout, shape):
     assert_close(C, gemm_oracle(layout, A, Bm), TOL[dtype], f"gemm {layout} {shape}")
 
 
+# Aligned shapes that take the streaming kernel whole, every element against the oracle: one and several slabs of K
+# (the DMA ring's prologue and its clamped look-ahead), one and several tiles of both tile widths (N a multiple of
+# 320 takes the 256 x 320 tile in the NT and NN forms), several row tiles.
+STREAM_SHAPES = [(256, 320, 64), (256, 640, 128), (512, 320, 192), (256, 256, 64), (512, 512, 128), (768, 960, 256)]
+
+
+@pytest.mark.parametrize("layout", [B.GEMM_NT, B.GEMM_NN, B.GEMM_TN])
+@pytest.mark.parametrize("shape", STREAM_SHAPES)
+def test_gemm_streaming_kernel_small_aligned_shapes(layout, shape):
+    Mm, N, K = shape
+    a_shape = (Mm, K) if layout != B.GEMM_TN else (K, Mm)
+    b_shape = (N, K) if layout == B.GEMM_NT else (K, N)
+    A, Bm = randn(a_shape, "bf16", 11), randn(b_shape, "bf16", 12, 0.3)
+    bias, res = randn((N,), "bf16", 13), randn((Mm, N), "bf16", 14)
+    want = gemm_oracle(layout, A, Bm)
+    C = torch.full((Mm, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_gemm(layout, dev(A), dev(Bm), C)
+    assert_close(C, want, TOL["bf16"], f"stream {layout} {shape}")
+    # the epilogue that goes through fp32 (bias + residual), and fp32 output
+    C.fill_(float("nan"))
+    M.mtnlg_gemm(layout, dev(A), dev(Bm), C, bias=dev(bias), aux=dev(res), epilogue=B.EPI_BIAS | B.EPI_RESIDUAL)
+    assert_close(C, want + to_np(bias) + to_np(res), TOL["bf16"], f"stream {layout} {shape} bias+residual")
+    C32 = torch.full((Mm, N), float("nan"), dtype=torch.float32, device="cuda")
+    M.mtnlg_gemm(layout, dev(A), dev(Bm), C32, epilogue=B.EPI_OUT_F32)
+    assert_close(C32, want, TOL["fp32"], f"stream {layout} {shape} f32 out")
+
+
 @pytest.mark.parametrize("layout", [B.GEMM_NT, B.GEMM_NN, B.GEMM_TN])
 @pytest.mark.parametrize("shape", [(520, 776, 4104), (256, 512, 2048)])
 def test_gemm_split_k_tail_with_workspace(layout, shape):
