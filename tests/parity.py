@@ -37,48 +37,62 @@ def to_np(t):
     return t.detach().to("cpu", torch.float64).numpy()
 
 
+def _as_rows(a):
+    """[everything else, last axis] view of a tensor (a vector is one row)."""
+    return a.reshape(1, -1) if a.dim() < 2 else a.reshape(-1, a.shape[-1])
+
+
+def compare(got, want, tol):
+    """(relative Frobenius error, element-wise ratio) of got against want in one chunked pass: the reference is
+    fp64 already, the device tensor is widened a block of rows at a time (the largest compared tensors have 1.3e9
+    elements); the arithmetic is fp64 on the host's cores.  The ratio is
+    max |got - want| / (ELEM_SIGMAS * tol * (scale + |want|)) with scale the largest of the global, row and column
+    rms of want; <= 1 passes."""
+    g_all = got.detach().cpu() if isinstance(got, torch.Tensor) else torch.from_numpy(np.asarray(got, dtype=np.float64))
+    w = torch.from_numpy(np.ascontiguousarray(np.asarray(want, dtype=np.float64).reshape(tuple(g_all.shape))))
+    g_all, w = _as_rows(g_all), _as_rows(w)
+    if w.numel() == 0:
+        return 0.0, 0.0
+    R, C = w.shape
+    step = max(1, (1 << 23) // C)
+    col_sq = torch.zeros(C, dtype=torch.float64)
+    row_sq = torch.empty(R, dtype=torch.float64)
+    for r0 in range(0, R, step):
+        sq = w[r0:r0 + step] ** 2
+        col_sq += sq.sum(0)
+        row_sq[r0:r0 + step] = sq.sum(1)
+    total = float(col_sq.sum())
+    rms = (total / w.numel()) ** 0.5
+    matrix = R > 1 and C > 1
+    col = torch.sqrt(col_sq / R)[None, :] if matrix else torch.zeros((1, C), dtype=torch.float64)
+    row = torch.sqrt(row_sq / C)[:, None] if matrix else torch.zeros((R, 1), dtype=torch.float64)
+    num, worst = 0.0, 0.0
+    for r0 in range(0, R, step):
+        sl = slice(r0, r0 + step)
+        d = (g_all[sl].to(torch.float64) - w[sl]).abs_()
+        num += float((d * d).sum())
+        if rms > 0.0:
+            local = torch.maximum(torch.maximum(row[sl], col), torch.tensor(rms, dtype=torch.float64))
+            d /= (local + w[sl].abs()) * (ELEM_SIGMAS * tol)
+            worst = max(worst, float(d.max()))
+    if total == 0.0:
+        return (0.0, 0.0) if num == 0.0 else (float("inf"), float("inf"))
+    return (num / total) ** 0.5, worst
+
+
 def rel_fro(got, want):
-    got = to_np(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
-    want = np.asarray(want, dtype=np.float64).reshape(got.shape)
-    den = np.linalg.norm(want)
-    num = np.linalg.norm(got - want)
-    if den == 0.0:
-        return 0.0 if num == 0.0 else float("inf")
-    return float(num / den)
+    return compare(got, want, 1.0)[0]
 
 
 def elementwise_ratio(got, want, tol):
-    """max over elements of |got - want| / (ELEM_SIGMAS * tol * (scale + |want|)) with scale the largest of the
-    global, row and column rms of want; <= 1 passes."""
-    got = to_np(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
-    want = np.asarray(want, dtype=np.float64).reshape(got.shape)
-    if want.size == 0:
-        return 0.0
-    diff = np.abs(got - want)
-    rms = float(np.sqrt(np.mean(want * want)))
-    if rms == 0.0:
-        return 0.0 if not diff.any() else float("inf")
-    scale = rms
-    if want.ndim >= 2 and want.shape[-1] > 1:
-        w2, d2 = want.reshape(-1, want.shape[-1]), diff.reshape(-1, want.shape[-1])
-        sq = w2 * w2
-        row = np.sqrt(sq.mean(axis=1, keepdims=True))
-        col = np.sqrt(sq.mean(axis=0, keepdims=True))
-        del sq
-        worst = 0.0
-        step = max(1, (1 << 24) // w2.shape[1])       # bounded temporaries on the 1e9-element tensors
-        for r0 in range(0, w2.shape[0], step):
-            sl = slice(r0, r0 + step)
-            local = np.maximum(np.maximum(row[sl], col), rms)
-            worst = max(worst, float((d2[sl] / (ELEM_SIGMAS * tol * (local + np.abs(w2[sl])))).max()))
-        return worst
-    return float((diff / (ELEM_SIGMAS * tol * (scale + np.abs(want)))).max())
+    return compare(got, want, tol)[1]
 
 
 def assert_close(got, want, tol, what, elementwise=True):
     assert torch.isfinite(got.float()).all() if isinstance(got, torch.Tensor) else True, f"{what}: non-finite"
-    err = rel_fro(got, want)
-    ratio = elementwise_ratio(got, want, tol) if elementwise else float("nan")
+    err, ratio = compare(got, want, tol)
+    if not elementwise:
+        ratio = float("nan")
     test = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
     RECORDS.append((test, what, err, tol, ratio, int(np.asarray(want).size)))
     assert err <= tol, f"{what}: relative Frobenius error {err:.3e} > {tol:.1e}"
