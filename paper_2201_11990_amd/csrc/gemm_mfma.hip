@@ -2,10 +2,11 @@
 //
 // Two kernels share the tile numbering, the split-K tail and the epilogue:
 //
-//  * gemm_stream_kernel (aligned problems: M, N multiples of 256, K of 64 -- every GEMM of the
-//    MT-NLG slice): 256x256 tile on 2 x 4 waves, v_mfma_f32_16x16x32_bf16, both operands moved
-//    global -> LDS by DMA through a ring of 2 + 3 stages with the loads spread over the slab,
-//    transposing LDS reads for row-contiguous operands.  Described at its definition.
+//  * gemm_stream_kernel (aligned problems: M a multiple of 256, N of the tile width, K of 64 -- every
+//    GEMM of the MT-NLG slice): 256x256 or 256x320 tile on 2 x 4 waves, v_mfma_f32_16x16x32_bf16, both
+//    operands moved global -> LDS by DMA through a ring of 2 + 3 (or 2 + 2) stages with the loads spread
+//    over the slab, transposing LDS reads for row-contiguous operands.  Described at its definition;
+//    gemm_mfma_pick_tile chooses kernel and tile shape per problem.
 //
 //  * gemm_bf16_kernel (everything else: ragged edges, K tails, small problems):
 //    v_mfma_f32_32x32x16_bf16, both operands brought into LDS as [row][k] tiles ("row" = m for
