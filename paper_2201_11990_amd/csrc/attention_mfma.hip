@@ -5,8 +5,8 @@
 //   backward with D_t = da_t . a_t :  dP = da v^T,  dS = P o (dP - D),
 //   dq = scale dS k,  dk = scale dS^T q,  dv = P^T da.
 //
-// Three kernels, one geometry.  A workgroup owns 128 rows of one side (queries for forward
-// and dq, keys for dk/dv), 16 or 32 per wave (eight or four waves), held in registers as MFMA
+// Three kernels, one geometry.  A workgroup owns 128 (or, forward only, 256) rows of one side (queries for
+// forward and dq, keys for dk/dv), 16 or 32 per wave on eight waves, held in registers as MFMA
 // B operands (groups of 16, one row per lane column); the other side streams through
 // LDS in tiles of 64 rows, brought in by LDS DMA (buffer_load ... lds, no staging
 // registers) three tiles deep, one workgroup barrier per tile.
@@ -192,7 +192,7 @@ __device__ __forceinline__ float quad_max(float v) {
 // of tiles, and while only one half has work in a tile it has the compute unit to itself.  With an
 // odd nb the middle block is alone in its workgroup and the other half only helps to move tiles.
 // Four waves of 32 rows (G = 2) keep consecutive 128-row blocks.
-template <int G>
+template <int G, int W = 8 / G>
 struct RowBlocks {
   int row0;        // first row of this wave
   int first_tile;  // lowest and highest 64-row block of the workgroup: the tile range that the
@@ -200,27 +200,33 @@ struct RowBlocks {
   bool idle;       // wave-uniform: this wave owns no rows
   __device__ RowBlocks(int s, int pair, int wave) {
     const int nb = (s + 63) / 64;
-    if (G == 2) {
+    if (W == 4) {
       row0 = pair * 128 + wave * 32;
       first_tile = 2 * pair;
       last_tile = 2 * pair + 1 < nb ? 2 * pair + 1 : nb - 1;
       idle = false;
     } else {
-      const int lo = pair, hi = nb - 1 - pair, half = wave >> 2;
-      row0 = (half ? hi : lo) * 64 + (wave & 3) * 16;
-      first_tile = lo;
-      last_tile = hi;
+      // eight waves: the two halves own blocks lo and hi of 64 G rows from opposite ends of the sequence
+      constexpr int TPB = G;   // 64-row tiles per block
+      const int nblk = (nb + TPB - 1) / TPB;
+      const int lo = pair, hi = nblk - 1 - pair, half = wave >> 2;
+      row0 = (half ? hi : lo) * (64 * G) + (wave & 3) * (16 * G);
+      first_tile = lo * TPB;
+      last_tile = hi * TPB + TPB - 1 < nb ? hi * TPB + TPB - 1 : nb - 1;
       idle = half && hi == lo;
     }
   }
   // workgroups along x for a sequence of s rows
-  static int grid(int s) { return G == 2 ? (s + 127) / 128 : ((s + 63) / 64 + 1) / 2; }
+  static int grid(int s) {
+    const int nb = (s + 63) / 64;
+    return W == 4 ? (s + 127) / 128 : ((nb + G - 1) / G + 1) / 2;
+  }
 };
 
 // ------------------------------------------------------------------ forward
-template <int D, int G>
-__global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
-                                                       bf16 *__restrict__ a, float *__restrict__ lse) {
+template <int D, int G, int W = 8 / G>
+__global__ __launch_bounds__(64 * W) void attn_fwd_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
+                                                      bf16 *__restrict__ a, float *__restrict__ lse) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
   constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
@@ -228,7 +234,7 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const RowBlocks<G> rb(s, blockIdx.x, wave);
+  const RowBlocks<G, W> rb(s, blockIdx.x, wave);
   const int qw = rb.row0;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
@@ -259,10 +265,10 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
   }
 
   const int ntiles = rb.last_tile + 1;
-  // Who brings what: with four waves (G = 2) wave w brings rows 16 w .. 16 w + 15 of the K tile and of
-  // the V tile; with eight (G = 1) waves 0-3 bring the K tile, waves 4-7 the V tile.
-  constexpr int IPW = G * T::NI;   // DMA instructions per wave and tile
-  const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
+  // Who brings what: with four waves wave w brings rows 16 w .. 16 w + 15 of the K tile and of
+  // the V tile; with eight, waves 0-3 bring the K tile, waves 4-7 the V tile.
+  constexpr int IPW = (W == 4 ? 2 : 1) * T::NI;   // DMA instructions per wave and tile
+  const int quarter = W == 4 ? wave : (wave & 3), half = W == 4 ? 0 : (wave >> 2);
   const dma_rsrc_t rk = dma_rsrc(base + D + half * D), rv = dma_rsrc(base + 2 * D);
   // DMA instruction i (of IPW) of tile t (clamped to the last one) into ring stage st.  A tile's
   // DMAs go out one per step of the first MFMA run of the tile before: a burst of them would hold
@@ -270,7 +276,7 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
   auto issue_one = [&](auto tag, int t, int st, int i) {
     constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    if (G == 1 || i < T::NI)
+    if (W == 8 || i < T::NI)
       T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + half * T::BYTES, quarter, lane, i);
     else
       T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, quarter, lane, i - T::NI);
@@ -414,11 +420,11 @@ __global__ __launch_bounds__(512 / G) void attn_fwd_kernel(int s, int n, float s
 }
 
 // ------------------------------------------------------------------ backward: dq (and D)
-template <int D, int G>
-__global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
-                                                          const bf16 *__restrict__ a, const float *__restrict__ lse,
-                                                          const bf16 *__restrict__ da, bf16 *__restrict__ dqkv,
-                                                          float *__restrict__ Dvec) {
+template <int D, int G, int W = 8 / G>
+__global__ __launch_bounds__(64 * W) void attn_bwd_dq_kernel(int s, int n, float scale, const bf16 *__restrict__ qkv,
+                                                         const bf16 *__restrict__ a, const float *__restrict__ lse,
+                                                         const bf16 *__restrict__ da, bf16 *__restrict__ dqkv,
+                                                         float *__restrict__ Dvec) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   using T = Tile<D>;
   constexpr int KK = D / 32, DB = D / 16, STAGE = 2 * T::BYTES;
@@ -426,7 +432,7 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, lr = lane & 15;
   const int64_t ld = (int64_t)n * 3 * D, pld = (int64_t)n * D;
   const bf16 *base = qkv + (int64_t)bi * s * ld + (int64_t)j * 3 * D;
-  const RowBlocks<G> rb(s, blockIdx.x, wave);
+  const RowBlocks<G, W> rb(s, blockIdx.x, wave);
   const int qw = rb.row0;
   const float c = scale * kLog2e;
   const typename T::Lane ln(lane);
@@ -465,13 +471,13 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dq_kernel(int s, int n, floa
 
   const int ntiles = rb.last_tile + 1;
   // tile DMAs as in the forward kernel
-  constexpr int IPW = G * T::NI;
-  const int quarter = G == 2 ? wave : (wave & 3), half = G == 2 ? 0 : (wave >> 2);
+  constexpr int IPW = (W == 4 ? 2 : 1) * T::NI;
+  const int quarter = W == 4 ? wave : (wave & 3), half = W == 4 ? 0 : (wave >> 2);
   const dma_rsrc_t rk = dma_rsrc(base + D + half * D), rv = dma_rsrc(base + 2 * D);
   auto issue_one = [&](auto tag, int t, int st, int i) {
     constexpr int TAG = decltype(tag)::value;
     const int tt = t < ntiles ? t : ntiles - 1;
-    if (G == 1 || i < T::NI)
+    if (W == 8 || i < T::NI)
       T::template dma_one<TAG>(rk, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + half * T::BYTES, quarter, lane, i);
     else
       T::template dma_one<TAG>(rv, tt * 64, s, (uint32_t)(ld * 2), smem_addr + st * STAGE + T::BYTES, quarter, lane, i - T::NI);
@@ -774,49 +780,76 @@ __global__ __launch_bounds__(512 / G) void attn_bwd_dkv_kernel(int s, int n, flo
   }
 }
 
-// Row groups of 16 per wave: 2 = four waves of 32 rows (every LDS fragment feeds two MFMAs, but
-// the kernel needs more than 256 registers and the compiler shuttles values between the two
-// register files), 1 = eight waves of 16 rows (twice the LDS reads, two waves per SIMD to overlap
-// the softmax arithmetic with the MFMAs, no register shuffling).  Measured at head size 160,
-// sequence 2048 (2 -> 1): forward 69 -> 54 us, dk/dv 119 -> 86 us, dq 77 -> 69 us.
-constexpr int FWD_G = 1, DQ_G = 1, DKV_G = 1;
+// Row groups of 16 per wave and waves per workgroup.  Four waves of 32 rows (every LDS fragment feeds two MFMAs, one
+// wave per SIMD with 512 registers) measured slower than eight waves of 16 rows (twice the LDS reads, two waves per
+// SIMD to overlap the softmax arithmetic with the MFMAs) at head size 160, sequence 2048: forward 69 against 54 us,
+// dk/dv 119 against 86 us, dq 77 against 69 us.  Eight waves of 32 rows need 256 rows per workgroup: the forward
+// kernel takes that shape when the problem has enough workgroups (see fwd_launch); the backward kernels do not fit
+// the 256 registers a wave has at eight waves.
+constexpr int DKV_G = 1;
 
-template <int D>
-int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
+// Forward with 32 rows per wave on eight waves (256 rows per workgroup): every K / V fragment read from LDS feeds two
+// MFMAs, which halves the kernel's LDS traffic -- its bound: each of the eight waves reads the whole K and V tile, the
+// V tile through half-rate transposing reads -- but halves the number of workgroups as well.  Taken when that still
+// leaves at least one workgroup per compute unit (the MT-NLG slice at micro-batch 1 has 16 heads x 8 = 128: it stays
+// with 16 rows per wave) and the head size is 128 or 160 (at 64 the variant measures 17 % slower).  Measured: 1.3B-shaped
+// layer (4 x 16 heads x 128) 168 -> 123 us, slice at micro-batch 4 167 -> 129 us, whole layer (128 heads) 326 -> 250 us.
+template <int D, int G>
+int fwd_launch_g(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
   constexpr int smem = 3 * 2 * 64 * D * 2;
   static unsigned long long attr_done = 0;
   int device;
   if (!attr_is_set(attr_done, &device)) {
-    if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D, FWD_G>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+    if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D, G, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
         hipSuccess)
       return MTNLG_HIP_ERROR;
     attr_mark_set(attr_done, device);
   }
   LaunchScope scope(MTNLG_K_ATTN_FWD, st);
-  attn_fwd_kernel<D, FWD_G><<<dim3(RowBlocks<FWD_G>::grid(s), n, b), 512 / FWD_G, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a,
-                                                                                    lse);
+  attn_fwd_kernel<D, G, 8><<<dim3(RowBlocks<G, 8>::grid(s), n, b), 512, smem, st>>>(s, n, scale, (const bf16 *)qkv, (bf16 *)a, lse);
+  return check_launch();
+}
+
+template <int D>
+int fwd_launch(int b, int s, int n, float scale, const void *qkv, void *a, float *lse, hipStream_t st) {
+  if (D >= 128 && (int64_t)RowBlocks<2, 8>::grid(s) * n * b >= 256) return fwd_launch_g<D, 2>(b, s, n, scale, qkv, a, lse, st);
+  return fwd_launch_g<D, 1>(b, s, n, scale, qkv, a, lse, st);
+}
+
+template <int D, int G>
+int bwd_dq_launch_g(int b, int s, int n, float scale, const void *qkv, const void *a, const float *lse, const void *da,
+                    void *dqkv, float *Dvec, hipStream_t st) {
+  constexpr int smem_dq = 3 * 2 * 64 * D * 2;
+  static unsigned long long attr_done = 0;
+  int device;
+  if (!attr_is_set(attr_done, &device)) {
+    if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D, G, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            smem_dq) != hipSuccess)
+      return MTNLG_HIP_ERROR;
+    attr_mark_set(attr_done, device);
+  }
+  attn_bwd_dq_kernel<D, G, 8><<<dim3(RowBlocks<G, 8>::grid(s), n, b), 512, smem_dq, st>>>(
+      s, n, scale, (const bf16 *)qkv, (const bf16 *)a, lse, (const bf16 *)da, (bf16 *)dqkv, Dvec);
   return check_launch();
 }
 
 template <int D>
 int bwd_launch(int b, int s, int n, float scale, const void *qkv, const void *a, const float *lse, const void *da,
                void *dqkv, void *ws, hipStream_t st) {
-  constexpr int smem_dq = 3 * 2 * 64 * D * 2, smem_dkv = 3 * (2 * 64 * D * 2 + 512);
+  constexpr int smem_dkv = 3 * (2 * 64 * D * 2 + 512);
   static unsigned long long attr_done = 0;
   int device;
   if (!attr_is_set(attr_done, &device)) {
-    if (hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<D, DQ_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            smem_dq) != hipSuccess ||
-        hipFuncSetAttribute((const void *)attn_bwd_dkv_kernel<D, DKV_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void *)attn_bwd_dkv_kernel<D, DKV_G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             smem_dkv) != hipSuccess)
       return MTNLG_HIP_ERROR;
     attr_mark_set(attr_done, device);
   }
   float *Dvec = (float *)ws;
   LaunchScope scope(MTNLG_K_ATTN_BWD, st);
-  attn_bwd_dq_kernel<D, DQ_G><<<dim3(RowBlocks<DQ_G>::grid(s), n, b), 512 / DQ_G, smem_dq, st>>>(
-      s, n, scale, (const bf16 *)qkv, (const bf16 *)a, lse, (const bf16 *)da, (bf16 *)dqkv, Dvec);
-  MTNLG_TRY(check_launch());
+  // 16 rows per wave in both backward kernels: with 32 the dq kernel spills at head size 128 (256 registers and 256
+  // bytes of scratch) and the dk/dv kernel does not fit at any
+  MTNLG_TRY((bwd_dq_launch_g<D, 1>(b, s, n, scale, qkv, a, lse, da, dqkv, Dvec, st)));
   attn_bwd_dkv_kernel<D, DKV_G><<<dim3(RowBlocks<DKV_G>::grid(s), n, b), 512 / DKV_G, smem_dkv, st>>>(
       s, n, scale, (const bf16 *)qkv, lse, Dvec, (const bf16 *)da, (bf16 *)dqkv);
   return check_launch();

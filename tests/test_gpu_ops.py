@@ -254,6 +254,36 @@ def test_attention_fwd_bwd(dtype, b, s, n, d):
         assert rel_fro(got[:, :, :, i], want[:, :, :, i]) <= tol, f"d{nm}"
 
 
+# Enough (sequence block, head, batch) workgroups for the forward kernel to take its 256-rows-per-workgroup shape
+# (32 rows per wave) at head sizes 128 and 160: an odd number of 64-row tiles whose last block hangs over the end
+# (s 150), an odd number of 128-row blocks, i.e. a middle block alone in its workgroup (s 257, 700 -> 3 and 6 blocks),
+# one block only (s 64, s 1), several tiles per block with a ragged end (s 1000).
+ATT_WIDE_CASES = [(8, 150, 64, 128), (4, 257, 64, 160), (2, 700, 64, 128), (16, 64, 16, 160), (8, 1, 32, 128),
+                  (2, 1000, 32, 160)]
+
+
+@pytest.mark.parametrize("b,s,n,d", ATT_WIDE_CASES)
+def test_attention_forward_with_32_rows_per_wave(b, s, n, d):
+    dims = oracle.Dims(hidden=8, heads=n, head_dim=d, ffn=8, seq=s, batch=b)
+    qkv = randn((b * s, 3 * n * d), "bf16", 30, 1.0)
+    scale = 1.0 / math.sqrt(d)
+    a = torch.full((b * s, n * d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((b, n, s), float("nan"), device="cuda")
+    M.mtnlg_attention_fwd(b, s, n, d, scale, dev(qkv), a, lse)
+    assert_close(a, oracle.attention_fwd(dims, to_np(qkv)), TOL["bf16"], "attention out")
+    q = to_np(qkv).reshape(b, s, n, 3, d)
+    S = np.einsum("bsnd,btnd->bnst", q[:, :, :, 0], q[:, :, :, 1]) * scale
+    S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    want_lse = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(to_np(lse) - want_lse).max() < 3e-3
+    # the backward kernels read what this forward wrote
+    da = randn((b * s, n * d), "bf16", 31)
+    ws = torch.empty(M.mtnlg_attention_bwd_workspace(b, s, n, d), dtype=torch.uint8, device="cuda")
+    dqkv = torch.full(qkv.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mtnlg_attention_bwd(b, s, n, d, scale, dev(qkv), a, lse, dev(da), dqkv, ws)
+    assert_close(dqkv, oracle.attention_bwd(dims, to_np(qkv), to_np(da)), TOL["bf16"], "attention dqkv")
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("kind", ["sharp", "rising", "falling", "constant"])
 def test_attention_with_hard_score_patterns(dtype, kind):
