@@ -193,8 +193,6 @@ int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, c
                    void *C, const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes,
                    hipStream_t stream, int prof_class = -1, int tile = -1);
 int gemm_mfma_pick_tile(int layout, int64_t M, int64_t N, int64_t K, bool have_workspace);
-// true when the problem takes the streaming kernel (aligned M, N, K)
-bool gemm_mfma_streams(int layout, int64_t M, int64_t N, int64_t K);
 size_t gemm_mfma_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K);
 int attention_fwd_simple(int dtype, int b, int s, int n, int d, float scale, const void *qkv,
                          void *a, float *lse, hipStream_t stream);

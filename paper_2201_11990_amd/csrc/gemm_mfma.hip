@@ -989,11 +989,6 @@ size_t gemm_mfma_workspace_bytes(int layout, int64_t M, int64_t N, int64_t K) {
   return plan_split(tiles256, (int)((K + BK - 1) / BK), 256, 256, 0).workspace;
 }
 
-bool gemm_mfma_streams(int layout, int64_t M, int64_t N, int64_t K) {
-  const int tile = gemm_mfma_pick_tile(layout, M, N, K, true);
-  return tile == GEMM_TILE_STREAM_256x256 || tile == GEMM_TILE_STREAM_256x320;
-}
-
 int gemm_mfma_bf16(int layout, int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C,
                    const void *bias, void *aux, uint32_t epi, void *ws, size_t ws_bytes, hipStream_t stream,
                    int prof_class, int tile) {
