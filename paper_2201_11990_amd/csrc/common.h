@@ -91,6 +91,15 @@ __device__ __forceinline__ void dma16(dma_rsrc_t rs, uint32_t lds_dst, uint32_t 
                "v"(byte_offset), "s"(rs), "n"(TAG)
                : "memory", "m0");
 }
+// ... with a further byte offset that is the same in every lane (a scalar register: instructions whose lane offsets
+// differ by uniform amounts share one vector register)
+template <int TAG = 0>
+__device__ __forceinline__ void dma16(dma_rsrc_t rs, uint32_t lds_dst, uint32_t byte_offset, uint32_t uniform_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %4 offen lds ; site %3" ::"s"(
+                   __builtin_amdgcn_readfirstlane(lds_dst)),
+               "v"(byte_offset), "s"(rs), "n"(TAG), "s"(__builtin_amdgcn_readfirstlane(uniform_offset))
+               : "memory", "m0");
+}
 template <int TAG = 0>
 __device__ __forceinline__ void dma4(dma_rsrc_t rs, uint32_t lds_dst, uint32_t byte_offset) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds ; site %3" ::"s"(

@@ -182,19 +182,29 @@ __device__ __forceinline__ void sched_pairs() {
   }
 }
 
-// Scheduling pipeline of one k-step of the streaming kernel: NM MFMAs, NR LDS fragment reads and NV
-// DMA instructions, spread as evenly as the counts allow (one item after each MFMA).
-template <int NM, int NR, int NV, int M = 0, int R = 0, int V = 0>
+// LDS reads that should have been issued after MFMA number m + 1 of a phase of nm MFMAs with nr reads.
+//   rbj == 0: spread evenly.
+//   rbj > 0 (last phase of a slab; MFMAs in groups of 4 per column block): the first group carries the nr - (nm / 4) rbj
+//   reads of the next A fragments, group g > 0 the rbj reads that refill the B fragments of column block g - 1, whose
+//   registers group g - 1 has just released; the last block's refill follows the last MFMA.
+constexpr int sched_reads_after(int m, int nm, int nr, int rbj) {
+  if (rbj == 0) return ((m + 1) * nr + nm - 1) / nm;
+  const int ra = nr - (nm / 4) * rbj, grp = m / 4, s = m % 4;
+  return grp == 0 ? ((s + 1) * ra + 3) / 4 : ra + (grp - 1) * rbj + ((s + 1) * rbj + 3) / 4;
+}
+
+// Scheduling pipeline of one phase of the streaming kernel: NM MFMAs, NR LDS fragment reads and NV
+// DMA instructions (spread as evenly as the counts allow, one item after each MFMA).
+template <int NM, int NR, int NV, int RBJ = 0, int M = 0, int R = 0, int V = 0>
 __device__ __forceinline__ void stream_sched() {
   if constexpr (M < NM) {
     __builtin_amdgcn_sched_group_barrier(SCHED_MFMA, 1, 0);
-    // after MFMA number M+1: reads so far should be ceil((M+1) NR / NM), loads ceil((M+1) NV / NM) - offset
-    constexpr int r_target = ((M + 1) * NR + NM - 1) / NM;
+    constexpr int r_target = sched_reads_after(M, NM, NR, RBJ);
     constexpr int v_target = ((2 * M + 1) * NV) / (2 * NM);   // loads trail the reads by half a slot
     constexpr int dr = r_target - R, dv = v_target - V;
     if constexpr (dr > 0) __builtin_amdgcn_sched_group_barrier(SCHED_DS_READ, dr, 0);
     if constexpr (dv > 0) __builtin_amdgcn_sched_group_barrier(0x020, dv, 0);
-    stream_sched<NM, NR, NV, M + 1, R + (dr > 0 ? dr : 0), V + (dv > 0 ? dv : 0)>();
+    stream_sched<NM, NR, NV, RBJ, M + 1, R + (dr > 0 ? dr : 0), V + (dv > 0 ? dv : 0)>();
   } else {
     if constexpr (R < NR) __builtin_amdgcn_sched_group_barrier(SCHED_DS_READ, NR - R, 0);
     if constexpr (V < NV) __builtin_amdgcn_sched_group_barrier(0x020, NV - V, 0);
@@ -477,7 +487,8 @@ template <int BM, int BN, bool AT, bool BT, bool PLAIN16>
 __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WGM = 2, WGN = 4, NWAVES = WGM * WGN;
-  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 16, TN = WN / 16, HM = TM / 2;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 16, TN = WN / 16;
+  static_assert(TM == 8, "four phases of two 16-row blocks");
   constexpr int A_STAGE = BM * BK * 2, B_STAGE = BN * BK * 2;
   constexpr int RING_B = (BM == 256 && BN == 256) ? 3 : 2;
   constexpr int A_RING = 2 * A_STAGE, B_RING = RING_B * B_STAGE;
@@ -497,48 +508,64 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   int tm, tn;
   tile_coords(g, pid, tm, tn);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave: a scalar
   const int wm = wave / WGN, wn = wave % WGN;
   const bf16 *Abase = AT ? g.A + m0 : g.A + m0 * g.lda;
   const bf16 *Bbase = BT ? g.B + n0 : g.B + n0 * g.ldb;
 
   // DMA addressing.  Instruction q of an operand fills LDS bytes [1024 q, 1024 q + 1024) of the stage, lane l
   // the 16 bytes at 16 l; wave w issues the instructions NI w .. NI w + NI - 1.
-  auto dma_offset = [&](int q, int64_t ld, bool transposed, int rows) -> uint32_t {
-    if (!transposed) {   // rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8
-      const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3);   // row % 8 == lane / 8
-      return (uint32_t)(row * ld * 2 + c * 16);
-    } else {             // unit 64 q + l of the stage: k-row (64 q + l) / UPR, position (64 q + l) % UPR
-      const int upr = rows / 8, i = 64 * q + lane;
-      const int k = i / upr, pos = i % upr;
-      const int u = upr == 32 ? tr_pos<32>(pos, k) : tr_pos<40>(pos, k);
-      return (uint32_t)(k * ld * 2 + u * 16);
-    }
+  //   K-contiguous operand: rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8.  A wave's instructions
+  //   differ by 8 rows, the same amount in every lane: one vector offset, the rest in the scalar offset.
+  //   Row-contiguous operand: unit 64 q + l of the stage, k-row (64 q + l) / UPR, position (64 q + l) % UPR;
+  //   one vector offset per instruction.
+  auto dma_offset_k = [&](int q, int64_t ld) -> uint32_t {
+    const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3);   // row % 8 == lane / 8
+    return (uint32_t)(row * ld * 2 + c * 16);
   };
-  uint32_t a_off[NIA], b_off[NIB];
+  auto dma_offset_t = [&](int q, int64_t ld, int rows) -> uint32_t {
+    const int upr = rows / 8, i = 64 * q + lane;
+    const int k = i / upr, pos = i % upr;
+    const int u = upr == 32 ? tr_pos<32>(pos, k) : tr_pos<40>(pos, k);
+    return (uint32_t)(k * ld * 2 + u * 16);
+  };
+  uint32_t a_off[AT ? NIA : 1], b_off[BT ? NIB : 1];
+  if constexpr (AT) {
 #pragma unroll
-  for (int i = 0; i < NIA; ++i) a_off[i] = dma_offset(wave * NIA + i, g.lda, AT, BM);
+    for (int i = 0; i < NIA; ++i) a_off[i] = dma_offset_t(wave * NIA + i, g.lda, BM);
+  } else {
+    a_off[0] = dma_offset_k(wave * NIA, g.lda);
+  }
+  if constexpr (BT) {
 #pragma unroll
-  for (int i = 0; i < NIB; ++i) b_off[i] = dma_offset(wave * NIB + i, g.ldb, BT, BN);
+    for (int i = 0; i < NIB; ++i) b_off[i] = dma_offset_t(wave * NIB + i, g.ldb, BN);
+  } else {
+    b_off[0] = dma_offset_k(wave * NIB, g.ldb);
+  }
+  const uint32_t a_step = (uint32_t)(16 * g.lda), b_step = (uint32_t)(16 * g.ldb);   // 8 rows of a K-contiguous operand
   // With a transposing LDS read in the loop the DMA goes out as inline assembly (see dma16: the
   // compiler would put a wait for all memory operations in front of those reads); otherwise
   // through the builtin, which the scheduling hints below can place.
-  auto issue = [&](const bf16 *base, const auto &off, char *stage, int i0, int i1) {
-    constexpr int NI = sizeof(off) / sizeof(off[0]);
-    char *dst = stage + wave * (NI * 1024);
+  auto issue = [&](const bf16 *base, const auto &off, uint32_t step, int ni, char *stage, int i0, int i1) {
+    constexpr int NOFF = sizeof(off) / sizeof(off[0]);
+    constexpr bool T = NOFF > 1;   // one offset per instruction: row-contiguous
+    char *dst = stage + wave * (ni * 1024);
     if constexpr (AT || BT) {
       const dma_rsrc_t rs = dma_rsrc(base);
       const uint32_t dst_addr = lds_address(dst);
 #pragma unroll
-      for (int i = 0; i < NI; ++i)
-        if (i >= i0 && i < i1) dma16(rs, dst_addr + i * 1024, off[i]);
+      for (int i = 0; i < 8; ++i)
+        if (i < ni && i >= i0 && i < i1) {
+          if constexpr (T) dma16(rs, dst_addr + i * 1024, off[i < NOFF ? i : 0]);
+          else dma16(rs, dst_addr + i * 1024, off[0], i * step);
+        }
     } else {
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
 #pragma unroll
-      for (int i = 0; i < NI; ++i)
-        if (i >= i0 && i < i1)
+      for (int i = 0; i < 8; ++i)
+        if (i < ni && i >= i0 && i < i1)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16,
-                                                   (int)off[i], 0, 0, 0);
+                                                   (int)off[0], (int)(i * step), 0, 0);
     }
   };
   auto a_at = [&](int64_t k0) { return AT ? Abase + k0 * g.lda : Abase + k0; };
@@ -574,39 +601,81 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
       return __builtin_bit_cast(bf16x8, v);
     }
   };
-  bf16x8 af[2][HM], bfr[2][TN];   // A: one buffer per half of the wave tile; B: one per k-step parity
-  auto read_a = [&](const char *abuf, int kk, int h) {
+  // A slab (two k-steps of 32) is four phases, one per pair of 16-row blocks of the wave tile; a phase issues both
+  // k-steps of each of its 2 x TN accumulator blocks back to back.  Two consecutive MFMAs on one accumulator, and
+  // beyond that consecutive MFMAs that share an operand, cost measurably less power than the same instructions
+  // in another order (a loop of nothing but MFMAs runs 4.5 % faster under the board's power limit with the pairs
+  // adjacent, 3 % faster with a shared operand than without), so the order below is a snake through
+  // (column block, row block, k-step) in which every step keeps the accumulator or one operand.
+  bf16x8 aq[2][2][2];   // A: [buffer = phase parity][row block of the pair][k-step]
+  bf16x8 bf[2][TN];     // B: [k-step][column block], all of the slab's
+  auto read_aq = [&](const char *abuf, int q) {   // A fragments of phase q (q == 4: phase 0 of the next slab)
 #pragma unroll
-    for (int i = 0; i < HM; ++i) af[h][i] = frag(abuf, wm * WM + (h * HM + i) * 16, kk, AT, BM);
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) aq[q & 1][rb][kk] = frag(abuf, wm * WM + (2 * (q & 3) + rb) * 16, kk, AT, BM);
   };
-  auto read_b = [&](const char *bbuf, int kk) {
+  auto read_bj = [&](const char *bbuf, int j) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[kk & 1][j] = frag(bbuf, wn * WN + j * 16, kk, BT, BN);
+    for (int kk = 0; kk < 2; ++kk) bf[kk][j] = frag(bbuf, wn * WN + j * 16, kk, BT, BN);
   };
-  auto mfma_phase = [&](int kk, int h) {
+  auto mfma_col = [&](int q, int j) {   // the 4 MFMAs of column block j in phase q
 #pragma unroll
-    for (int i = 0; i < HM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[h * HM + i][j] =   // B fragment first: the block comes out transposed, see the epilogue
-            __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk & 1][j], af[h][i], acc[h * HM + i][j], 0, 0, 0);
+    for (int step = 0; step < 4; ++step) {
+      const int t = (j & 1) ? 3 - step : step;   // (rb, kk): (0,0) (0,1) (1,1) (1,0), backwards for odd j
+      const int rb = t >> 1, kk = (t & 1) ^ rb;
+      acc[2 * q + rb][j] =   // B fragment first: the block comes out transposed, see the epilogue
+          __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[kk][j], aq[q & 1][rb][kk], acc[2 * q + rb][j], 0, 0, 0);
+    }
   };
 
   const int nk = slab1 - slab0;
   auto slab_k = [&](int it) { return (int64_t)(slab0 + (it < nk ? it : nk - 1)) * BK; };
   char *const aring = smem, *const bring = smem + A_RING;
-  constexpr int RA = (AT ? 2 : 1) * HM, RB = (BT ? 2 : 1) * TN;   // LDS read instructions of an A half / of B
+  constexpr int NM = 4 * TN;                                  // MFMAs of a phase
+  constexpr int RAQ = (AT ? 2 : 1) * 4, RBJ = (BT ? 2 : 1) * 2;   // LDS read instructions of read_aq / read_bj
   int a_cur = 0, b_cur = 0;   // ring offsets of slab `it`
+
+  // Phases 0 .. 2 read the A fragments of the next phase; phase 3, after the slab's one barrier, those of phase 0
+  // of the next slab and, column block by column block as its MFMAs release the registers, the next slab's B
+  // fragments.  dma(): the phase's share of the DMA instructions.
+  auto phase = [&](auto PH, const char *a_stage, const char *a_next, const char *b_next, auto dma, auto NDMA) {
+    constexpr int q = decltype(PH)::value, ndma = decltype(NDMA)::value;
+    if constexpr (q < 3) {
+      // The two waves of a SIMD take turns on the matrix pipe one phase at a time: the wave that
+      // is behind (counted from the barrier) has the higher issue priority.
+      __builtin_amdgcn_s_setprio(2 - q);
+      read_aq(a_stage, q + 1);
+      dma();
+#pragma unroll
+      for (int j = 0; j < TN; ++j) mfma_col(q, j);
+      stream_sched<NM, RAQ, ndma>();
+    } else {
+      __builtin_amdgcn_s_setprio(3);
+      __builtin_amdgcn_sched_barrier(0);
+      read_aq(a_next, 4);
+      dma();
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        mfma_col(3, j);
+        read_bj(b_next, j);
+      }
+      stream_sched<NM, RAQ + TN * RBJ, ndma, RBJ>();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using std::integral_constant;
 
   if constexpr (RING_B == 3) {
     // prologue: A slab 0, B slabs 0 and 1, first half of A slab 1
-    issue(a_at(slab_k(0)), a_off, aring, 0, NIA);
-    issue(b_at(slab_k(0)), b_off, bring, 0, NIB);
-    issue(b_at(slab_k(1)), b_off, bring + B_STAGE, 0, NIB);
-    issue(a_at(slab_k(1)), a_off, aring + A_STAGE, 0, NIA / 2);
+    issue(a_at(slab_k(0)), a_off, a_step, NIA, aring, 0, NIA);
+    issue(b_at(slab_k(0)), b_off, b_step, NIB, bring, 0, NIB);
+    issue(b_at(slab_k(1)), b_off, b_step, NIB, bring + B_STAGE, 0, NIB);
+    issue(a_at(slab_k(1)), a_off, a_step, NIA, aring + A_STAGE, 0, NIA / 2);
     wait_dma_and_barrier<NIB + NIA / 2>();   // A 0, B 0 landed
-    read_a(aring, 0, 0);
-    read_b(bring, 0);
+    read_aq(aring, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) read_bj(bring, j);
     for (int it = 0; it < nk; ++it) {
       const int a_nxt = a_cur ^ A_STAGE;
       const int b_nxt = b_cur + B_STAGE >= B_RING ? b_cur + B_STAGE - B_RING : b_cur + B_STAGE;
@@ -614,35 +683,16 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
       // phase 0: second half of A slab it+1 (into the stage slab it-1 left at the last barrier)
       // phases 1, 2: B slab it+2 into the ring stage that held slab it-1
       // phase 3 (after the barrier): first half of A slab it+2 into the stage slab it just left
-#pragma unroll
-      for (int ph = 0; ph < 4; ++ph) {
-        const int kk = ph >> 1, h = ph & 1;
-        // The two waves of a SIMD take turns on the matrix pipe one phase at a time: the wave that
-        // is behind (counted from the barrier) has the higher issue priority.
-        if (ph == 0) __builtin_amdgcn_s_setprio(2);
-        else if (ph == 1) __builtin_amdgcn_s_setprio(1);
-        else if (ph == 2) __builtin_amdgcn_s_setprio(0);
-        if (ph == 3) {
-          // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
-          wait_dma_and_barrier<NIB>();
-          __builtin_amdgcn_s_setprio(3);
-          __builtin_amdgcn_sched_barrier(0);
-          read_a(aring + a_nxt, 0, 0);
-          read_b(bring + b_nxt, 0);
-        } else if (h == 0) {
-          read_a(aring + a_cur, kk, 1);
-        } else {
-          read_a(aring + a_cur, kk + 1, 0);
-          read_b(bring + b_cur, kk + 1);
-        }
-        if (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, NIA / 2, NIA);
-        else if (ph < 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_nn, (ph - 1) * (NIB / 2), ph * (NIB / 2));
-        else issue(a_at(slab_k(it + 2)), a_off, aring + a_cur, 0, NIA / 2);
-        mfma_phase(kk, h);
-        if (h == 0) stream_sched<HM * TN, RA, NIA / 2>();
-        else stream_sched<HM * TN, RA + RB, NIA / 2>();
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      phase(integral_constant<int, 0>{}, aring + a_cur, nullptr, nullptr,
+            [&] { issue(a_at(slab_k(it + 1)), a_off, a_step, NIA, aring + a_nxt, NIA / 2, NIA); }, integral_constant<int, NIA / 2>{});
+      phase(integral_constant<int, 1>{}, aring + a_cur, nullptr, nullptr,
+            [&] { issue(b_at(slab_k(it + 2)), b_off, b_step, NIB, bring + b_nn, 0, NIB / 2); }, integral_constant<int, NIB / 2>{});
+      phase(integral_constant<int, 2>{}, aring + a_cur, nullptr, nullptr,
+            [&] { issue(b_at(slab_k(it + 2)), b_off, b_step, NIB, bring + b_nn, NIB / 2, NIB); }, integral_constant<int, NIB / 2>{});
+      // slab it+1 is complete once only the DMAs of B slab it+2 are outstanding
+      wait_dma_and_barrier<NIB>();
+      phase(integral_constant<int, 3>{}, nullptr, aring + a_nxt, bring + b_nxt,
+            [&] { issue(a_at(slab_k(it + 2)), a_off, a_step, NIA, aring + a_cur, 0, NIA / 2); }, integral_constant<int, NIA / 2>{});
       a_cur = a_nxt;
       b_cur = b_nxt;
     }
@@ -652,41 +702,23 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     // barrier (phase 3), A in phases 0 and 1 of slab it+1; slab it+1 has to be complete at the barrier of
     // slab it+1, when nothing else is in flight.
     constexpr int A_FIRST = (NIA + 1) / 2;
-    issue(a_at(slab_k(0)), a_off, aring, 0, NIA);
-    issue(b_at(slab_k(0)), b_off, bring, 0, NIB);
-    issue(b_at(slab_k(1)), b_off, bring + B_STAGE, 0, NIB);
+    issue(a_at(slab_k(0)), a_off, a_step, NIA, aring, 0, NIA);
+    issue(b_at(slab_k(0)), b_off, b_step, NIB, bring, 0, NIB);
+    issue(b_at(slab_k(1)), b_off, b_step, NIB, bring + B_STAGE, 0, NIB);
     wait_dma_and_barrier<NIB>();   // A 0, B 0 landed
-    read_a(aring, 0, 0);
-    read_b(bring, 0);
+    read_aq(aring, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) read_bj(bring, j);
     for (int it = 0; it < nk; ++it) {
       const int a_nxt = a_cur ^ A_STAGE, b_nxt = b_cur ^ B_STAGE;
-      auto phase = [&](auto PH) {
-        constexpr int ph = decltype(PH)::value, kk = ph >> 1, h = ph & 1;
-        constexpr int ndma = ph == 0 ? A_FIRST : ph == 1 ? NIA - A_FIRST : ph == 3 ? NIB : 0;
-        if constexpr (ph < 3) __builtin_amdgcn_s_setprio(2 - ph);
-        if constexpr (ph == 3) {
-          wait_dma_and_barrier<0>();   // slab it+1 complete
-          __builtin_amdgcn_s_setprio(3);
-          __builtin_amdgcn_sched_barrier(0);
-          read_a(aring + a_nxt, 0, 0);
-          read_b(bring + b_nxt, 0);
-        } else if constexpr (h == 0) {
-          read_a(aring + a_cur, kk, 1);
-        } else {
-          read_a(aring + a_cur, kk + 1, 0);
-          read_b(bring + b_cur, kk + 1);
-        }
-        if constexpr (ph == 0) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, 0, A_FIRST);
-        else if constexpr (ph == 1) issue(a_at(slab_k(it + 1)), a_off, aring + a_nxt, A_FIRST, NIA);
-        else if constexpr (ph == 3) issue(b_at(slab_k(it + 2)), b_off, bring + b_cur, 0, NIB);
-        mfma_phase(kk, h);
-        stream_sched<HM * TN, h == 0 ? RA : RA + RB, ndma>();
-        __builtin_amdgcn_sched_barrier(0);
-      };
-      phase(std::integral_constant<int, 0>{});
-      phase(std::integral_constant<int, 1>{});
-      phase(std::integral_constant<int, 2>{});
-      phase(std::integral_constant<int, 3>{});
+      phase(integral_constant<int, 0>{}, aring + a_cur, nullptr, nullptr,
+            [&] { issue(a_at(slab_k(it + 1)), a_off, a_step, NIA, aring + a_nxt, 0, A_FIRST); }, integral_constant<int, A_FIRST>{});
+      phase(integral_constant<int, 1>{}, aring + a_cur, nullptr, nullptr,
+            [&] { issue(a_at(slab_k(it + 1)), a_off, a_step, NIA, aring + a_nxt, A_FIRST, NIA); }, integral_constant<int, NIA - A_FIRST>{});
+      phase(integral_constant<int, 2>{}, aring + a_cur, nullptr, nullptr, [] {}, integral_constant<int, 0>{});
+      wait_dma_and_barrier<0>();   // slab it+1 complete
+      phase(integral_constant<int, 3>{}, nullptr, aring + a_nxt, bring + b_nxt,
+            [&] { issue(b_at(slab_k(it + 2)), b_off, b_step, NIB, bring + b_cur, 0, NIB); }, integral_constant<int, NIB>{});
       a_cur = a_nxt;
       b_cur = b_nxt;
     }
