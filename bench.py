@@ -32,7 +32,7 @@ def measured_peaks(x, reps=5):
 
     import paper_2201_11990_amd as M
 
-    wgs, iters = 256 * 4, 6000
+    wgs, iters = 256 * 4, 3000
     n = M.mtnlg_calibrate_mfma_operand_bytes(wgs) // 2
     ops = x.reshape(-1)
     ops = ops[:n].contiguous() if ops.numel() >= n else torch.randn(n, device=x.device).bfloat16()

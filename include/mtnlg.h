@@ -382,8 +382,8 @@ int mtnlg_profile_read(int32_t *launches /*[MTNLG_K_CLASSES]*/, float *ms /*[MTN
 /* --- measurement aids: what the chip sustains, with the benchmark's data, on the two resources that
  *     bound the layer's kernels (the throughput figures of the paper's Section 2.4 are fractions of a peak;
  *     these give the peak as measured next to the nominal one) ----------------------------------------------
- * mtnlg_calibrate_mfma: `workgroups` workgroups of 8 waves run `iters` rounds of 8 bf16 matrix-core
- * instructions (16x16x32, fp32 accumulate) each on fragments taken from `operands` (device, bf16,
+ * mtnlg_calibrate_mfma: `workgroups` workgroups of 8 waves run `iters` rounds of 16 bf16 matrix-core
+ * instructions (16x16x32, fp32 accumulate; issued in the order the GEMM kernel uses) each on fragments taken from `operands` (device, bf16,
  * mtnlg_calibrate_mfma_operand_bytes(workgroups) bytes, any finite values: the clock the power limit allows
  * depends on the data); nothing else runs in the loop.  out: device float[workgroups * 512], written.  The
  * work is mtnlg_calibrate_mfma_flops(workgroups, iters) FLOP; the caller times the launch.

@@ -3,27 +3,32 @@
 //
 //  * mtnlg_calibrate_mfma: a loop of nothing but v_mfma_f32_16x16x32_bf16 (the instruction of the GEMM and
 //    attention kernels) on the caller's operands, 8 waves per compute unit (two per SIMD, as in the GEMM), every
-//    wave cycling through 4 x 2 fragments and 8 accumulator blocks so that operands change from one
-//    instruction to the next.  No LDS, no memory traffic inside the loop: its rate is the matrix pipes' rate
-//    at the clock the board's power limit allows for this data.
+//    wave working on 4 x 2 accumulator blocks with two k-steps of operand fragments, in the order the GEMM kernel
+//    issues them: both k-steps of a block back to back, neighbouring instructions sharing an operand (the order
+//    matters: under the power limit this one sustains 8 % more than k-step after k-step).  No LDS, no memory
+//    traffic inside the loop: its rate is the matrix pipes' rate at the clock the board's power limit allows for
+//    this data.
 //  * mtnlg_calibrate_copy: a plain streaming copy, 16 bytes per lane: the HBM rate a kernel of this library
 //    can expect, and a kernel of known size to scale the profiler's byte counters by.
 #include "common.h"
 
 namespace mtnlg {
 
-constexpr int CAL_WAVES = 8, CAL_NA = 4, CAL_NB = 2;
+constexpr int CAL_WAVES = 8, CAL_NA = 4, CAL_NB = 2, CAL_KSTEPS = 2;
 
 __global__ __launch_bounds__(64 * CAL_WAVES, 1) void calibrate_mfma_kernel(const bf16 *__restrict__ operands, int iters,
                                                                            float *__restrict__ out) {
-  // every thread takes its own 6 fragments of 8 values from the operand buffer
+  // every thread takes its own 12 fragments of 8 values from the operand buffer
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const bf16x8 *src = reinterpret_cast<const bf16x8 *>(operands) + t * (CAL_NA + CAL_NB);
-  bf16x8 a[CAL_NA], b[CAL_NB];
+  const bf16x8 *src = reinterpret_cast<const bf16x8 *>(operands) + t * (CAL_KSTEPS * (CAL_NA + CAL_NB));
+  bf16x8 a[CAL_KSTEPS][CAL_NA], b[CAL_KSTEPS][CAL_NB];
 #pragma unroll
-  for (int i = 0; i < CAL_NA; ++i) a[i] = src[i];
+  for (int k = 0; k < CAL_KSTEPS; ++k) {
 #pragma unroll
-  for (int j = 0; j < CAL_NB; ++j) b[j] = src[CAL_NA + j];
+    for (int i = 0; i < CAL_NA; ++i) a[k][i] = src[k * (CAL_NA + CAL_NB) + i];
+#pragma unroll
+    for (int j = 0; j < CAL_NB; ++j) b[k][j] = src[k * (CAL_NA + CAL_NB) + CAL_NA + j];
+  }
   f32x4 acc[CAL_NA][CAL_NB];
 #pragma unroll
   for (int i = 0; i < CAL_NA; ++i)
@@ -32,11 +37,15 @@ __global__ __launch_bounds__(64 * CAL_WAVES, 1) void calibrate_mfma_kernel(const
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
   for (int it = 0; it < iters; ++it) {
+    // a snake through (i, j, k-step): every step keeps the accumulator or one operand
 #pragma unroll
-    for (int i = 0; i < CAL_NA; ++i)
-#pragma unroll
-      for (int j = 0; j < CAL_NB; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int n = 0; n < CAL_NA * CAL_NB * CAL_KSTEPS; ++n) {
+      const int i = n / (CAL_NB * CAL_KSTEPS);
+      const int m = (i & 1) ? CAL_NB * CAL_KSTEPS - 1 - n % (CAL_NB * CAL_KSTEPS) : n % (CAL_NB * CAL_KSTEPS);
+      const int j = m / CAL_KSTEPS, k = (m % CAL_KSTEPS) ^ (j & 1);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[k][i], b[k][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   float s = 0.0f;
 #pragma unroll
@@ -60,12 +69,12 @@ using namespace mtnlg;
 extern "C" {
 
 size_t mtnlg_calibrate_mfma_operand_bytes(int workgroups) {
-  return workgroups > 0 ? (size_t)workgroups * 64 * CAL_WAVES * (CAL_NA + CAL_NB) * 16 : 0;
+  return workgroups > 0 ? (size_t)workgroups * 64 * CAL_WAVES * (CAL_KSTEPS * (CAL_NA + CAL_NB)) * 16 : 0;
 }
 
 int64_t mtnlg_calibrate_mfma_flops(int workgroups, int iters) {
   if (workgroups <= 0 || iters <= 0) return 0;
-  return (int64_t)workgroups * CAL_WAVES * iters * (CAL_NA * CAL_NB) * (2LL * 16 * 16 * 32);
+  return (int64_t)workgroups * CAL_WAVES * iters * (CAL_NA * CAL_NB * CAL_KSTEPS) * (2LL * 16 * 16 * 32);
 }
 
 int mtnlg_calibrate_mfma(int workgroups, int iters, const void *operands, float *out, void *stream) {
