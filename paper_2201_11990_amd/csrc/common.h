@@ -129,6 +129,29 @@ __device__ __forceinline__ float gelu_grad_f(float z, bool erf_form) {
   return 0.5f * (1.0f + th) + 0.5f * z * (1.0f - th * th) * dinner;
 }
 
+// The tanh form again for the epilogue of the bf16 MFMA GEMMs, where the library tanhf (some 40 instructions an
+// element) would cost a 256 x 320 tile 25 us of vector ALU time with the matrix pipes idle.  With
+// s = 1 / (1 + exp(-2 u)), u = sqrt(2/pi) (z + 0.044715 z^3):  0.5 (1 + tanh u) = s, so GeLU(z) = z s and
+// GeLU'(z) = s + 2 z u' s (1 - s), 1 - s = exp(-2 u) s.  Hardware exp2 and reciprocal (1 ulp each): relative error
+// of a few 1e-7, two orders below the rounding of the bf16 result; no cancellation for very negative z, unlike
+// 1 + tanh.  The exponent is clamped so that exp(-2 u) s stays finite.  8 and 13 instructions an element.
+__device__ __forceinline__ float gelu_sigmoid_f(float z, float z2, float &e) {   // returns s, e = exp(-2 u)
+  constexpr float K1 = -2.0f * 1.4426950408889634f * 0.79788456080286536f, K3 = K1 * 0.044715f;   // -2 u log2(e) = z (K1 + K3 z^2)
+  e = __builtin_amdgcn_exp2f(fminf(z * (K1 + K3 * z2), 115.0f));
+  return __builtin_amdgcn_rcpf(1.0f + e);
+}
+__device__ __forceinline__ float gelu_tanh_fast_f(float z) {
+  float e;
+  return z * gelu_sigmoid_f(z, z * z, e);
+}
+__device__ __forceinline__ float gelu_tanh_grad_fast_f(float z) {
+  constexpr float D1 = 2.0f * 0.79788456080286536f, D3 = D1 * 3.0f * 0.044715f;   // 2 u' = D1 + D3 z^2
+  const float z2 = z * z;
+  float e;
+  const float s = gelu_sigmoid_f(z, z2, e);
+  return s + (z * (D1 + D3 * z2)) * (e * s) * s;
+}
+
 // GEMM epilogue shared by the GEMM kernels: bias, GeLU (pre-activation kept in aux),
 // residual from aux, accumulate, fp32 or storage-dtype output.  One element at a time.
 struct EpiArgs {

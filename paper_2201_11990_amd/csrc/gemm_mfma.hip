@@ -221,8 +221,10 @@ template <int ROWS, int NTHR, bool D>
 struct Loader<ROWS, NTHR, true, D> : LoadT<ROWS, NTHR> {};
 
 // Bias / GeLU / residual / accumulate / store for 8 consecutive outputs of row m at column n.
-__device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t n, float (&v)[8]) {
-  const uint32_t flags = g.ea.flags;
+// flags: the epilogue flags to apply (a caller that has added the bias already passes them without it);
+// aux_in: the 8 aux values of this position if the caller has loaded them already, else nullptr.
+__device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t n, float (&v)[8], uint32_t flags,
+                                          const bf16x8 *aux_in = nullptr) {
   const int64_t off = m * g.ldc + n;
   float t[8];
   if (flags & MTNLG_EPI_BIAS) {
@@ -232,20 +234,33 @@ __device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t 
   }
   if (flags & MTNLG_EPI_GELU) {
     store8(static_cast<bf16 *>(g.ea.aux) + off, v);
-    const bool erf_form = (flags & MTNLG_EPI_GELU_ERF) != 0;
+    if (flags & MTNLG_EPI_GELU_ERF) {   // the form is chosen per group of 8, not per element
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e], erf_form);
+      for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e], true);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = gelu_tanh_fast_f(v[e]);
+    }
   }
-  if (flags & MTNLG_EPI_RESIDUAL) {
-    load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
+  if (flags & (MTNLG_EPI_RESIDUAL | MTNLG_EPI_GELU_GRAD)) {
+    if (aux_in) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += t[e];
-  }
-  if (flags & MTNLG_EPI_GELU_GRAD) {
-    load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
-    const bool erf_form = (flags & MTNLG_EPI_GELU_ERF) != 0;
+      for (int e = 0; e < 8; ++e) t[e] = (float)(*aux_in)[e];
+    } else {
+      load8(static_cast<const bf16 *>(g.ea.aux) + off, t);
+    }
+    if (flags & MTNLG_EPI_RESIDUAL) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(t[e], erf_form);
+      for (int e = 0; e < 8; ++e) v[e] += t[e];
+    } else {
+      if (flags & MTNLG_EPI_GELU_ERF) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(t[e], true);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= gelu_tanh_grad_fast_f(t[e]);
+      }
+    }
   }
   if (flags & MTNLG_EPI_OUT_F32) {
     float *c = static_cast<float *>(g.C) + off;
@@ -264,6 +279,9 @@ __device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t 
     }
     store8(c, v);
   }
+}
+__device__ __forceinline__ void epilogue8(const GemmArgs &g, int64_t m, int64_t n, float (&v)[8]) {
+  epilogue8(g, m, n, v, g.ea.flags);
 }
 
 // Tile order: tiles are numbered so that 32 consecutive ids form an 8 (m) x 4 (n)
@@ -788,7 +806,38 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     }
   } else {
     constexpr int PITCH = WN + 4;   // floats; 68 and 84 both leave 16-byte block stores of 16 rows conflict-free
+    constexpr int NP = WM / RP;
     float *patch = reinterpret_cast<float *>(smem) + ewave * (RP * PITCH);
+    const bool whole = part_id < 0;
+    // The bias joins in the accumulator layout (4 consecutive columns per lane), and the values a residual or a
+    // GeLU' read from aux are fetched two passes ahead, in the registers the accumulators of finished passes
+    // leave: no pass waits for global memory except the first.
+    const uint32_t flags = whole ? g.ea.flags : 0u;
+    bf16x4 bias_h[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bias_h[j][e] = (bf16)0.0f;
+      if (flags & MTNLG_EPI_BIAS)
+        bias_h[j] = *reinterpret_cast<const bf16x4 *>(static_cast<const bf16 *>(g.ea.bias) + n0 + ewn * WN + j * 16 + 4 * (elane >> 4));
+    }
+    const bool pre_aux = (flags & (MTNLG_EPI_RESIDUAL | MTNLG_EPI_GELU_GRAD)) != 0;
+    const bf16 *aux_base = static_cast<const bf16 *>(g.ea.aux) + (m0 + ewm * WM) * g.ldc + n0 + ewn * WN;
+    bf16x8 pre[NP][NRD];
+    auto preload = [&](auto P) {
+      constexpr int p = decltype(P)::value;
+      if constexpr (p < NP) {
+        if (pre_aux) {
+#pragma unroll
+          for (int t = 0; t < NRD; ++t) {
+            const int q = t * 64 + elane, row = q / SEG, cv = q % SEG;
+            pre[p][t] = *reinterpret_cast<const bf16x8 *>(aux_base + (int64_t)(p * RP + row) * g.ldc + cv * 8);
+          }
+        }
+      }
+    };
+    preload(std::integral_constant<int, 0>{});
+    preload(std::integral_constant<int, 1>{});
     // one pass; instantiated per pass number so that the accumulator blocks are always named at compile time
     // (a pass loop this large is not unrolled on request, and a rolled one would index the registers dynamically)
     auto pass = [&](auto P) {
@@ -796,8 +845,13 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
       for (int i = 0; i < RP / 16; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          *reinterpret_cast<f32x4 *>(patch + ((elane & 15) + i * 16) * PITCH + j * 16 + 4 * (elane >> 4)) = acc[p * (RP / 16) + i][j];
+        for (int j = 0; j < TN; ++j) {
+          f32x4 o = acc[p * (RP / 16) + i][j];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] += (float)bias_h[j][e];
+          *reinterpret_cast<f32x4 *>(patch + ((elane & 15) + i * 16) * PITCH + j * 16 + 4 * (elane >> 4)) = o;
+        }
+      preload(std::integral_constant<int, p + 2>{});
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
       for (int t = 0; t < NRD; ++t) {
@@ -808,10 +862,10 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
         const int trow = ewm * WM + p * RP + row, tcol = ewn * WN + cv * 8;   // position in the tile
-        if (part_id >= 0) {  // K-part of a tail tile: raw fp32 partial, summed by splitk_reduce_kernel
+        if (!whole) {  // K-part of a tail tile: raw fp32 partial, summed by splitk_reduce_kernel
           store8(g.partial + (int64_t)part_id * (BM * BN) + trow * BN + tcol, v);
         } else {
-          epilogue8(g, m0 + trow, n0 + tcol, v);
+          epilogue8(g, m0 + trow, n0 + tcol, v, flags & ~MTNLG_EPI_BIAS, pre_aux ? &pre[p][t] : nullptr);
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // patch is rewritten by the next pass
