@@ -535,8 +535,10 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   // the 16 bytes at 16 l; wave w issues the instructions NI w .. NI w + NI - 1.
   //   K-contiguous operand: rows 8q .. 8q+7, lane l: row 8q + l/8, chunk position l%8.  A wave's instructions
   //   differ by 8 rows, the same amount in every lane: one vector offset, the rest in the scalar offset.
-  //   Row-contiguous operand: unit 64 q + l of the stage, k-row (64 q + l) / UPR, position (64 q + l) % UPR;
-  //   one vector offset per instruction.
+  //   Row-contiguous operand: unit 64 q + l of the stage, k-row (64 q + l) / UPR, position (64 q + l) % UPR.
+  //   32 units per k-row: instruction i of a wave covers k-rows 8 w + 2 i, + 1 and the permutation depends on the
+  //   k-row through k & 3 and bit 3 only, so instructions i and i + 2 differ by 4 k-rows in every lane: two vector
+  //   offsets, the rest in the scalar offset.  40 units per k-row: one vector offset per instruction.
   auto dma_offset_k = [&](int q, int64_t ld) -> uint32_t {
     const int row = 8 * q + (lane >> 3), c = (lane & 7) ^ (lane >> 3);   // row % 8 == lane / 8
     return (uint32_t)(row * ld * 2 + c * 16);
@@ -547,26 +549,20 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
     const int u = upr == 32 ? tr_pos<32>(pos, k) : tr_pos<40>(pos, k);
     return (uint32_t)(k * ld * 2 + u * 16);
   };
-  uint32_t a_off[AT ? NIA : 1], b_off[BT ? NIB : 1];
-  if constexpr (AT) {
+  constexpr int A_NOFF = !AT ? 1 : 2, B_NOFF = !BT ? 1 : BN == 256 ? 2 : NIB;
+  static_assert(BM == 256 && NIA == 4, "the A side assumes 256 rows");
+  uint32_t a_off[A_NOFF], b_off[B_NOFF];
 #pragma unroll
-    for (int i = 0; i < NIA; ++i) a_off[i] = dma_offset_t(wave * NIA + i, g.lda, BM);
-  } else {
-    a_off[0] = dma_offset_k(wave * NIA, g.lda);
-  }
-  if constexpr (BT) {
+  for (int i = 0; i < A_NOFF; ++i) a_off[i] = AT ? dma_offset_t(wave * NIA + i, g.lda, BM) : dma_offset_k(wave * NIA, g.lda);
 #pragma unroll
-    for (int i = 0; i < NIB; ++i) b_off[i] = dma_offset_t(wave * NIB + i, g.ldb, BN);
-  } else {
-    b_off[0] = dma_offset_k(wave * NIB, g.ldb);
-  }
-  const uint32_t a_step = (uint32_t)(16 * g.lda), b_step = (uint32_t)(16 * g.ldb);   // 8 rows of a K-contiguous operand
+  for (int i = 0; i < B_NOFF; ++i) b_off[i] = BT ? dma_offset_t(wave * NIB + i, g.ldb, BN) : dma_offset_k(wave * NIB, g.ldb);
+  // scalar offset of instruction i: K-contiguous 8 i rows; row-contiguous with 32 units 4 (i / 2) k-rows
+  const uint32_t a_step = (uint32_t)((AT ? 8 : 16) * g.lda), b_step = (uint32_t)((BT ? 8 : 16) * g.ldb);
   // With a transposing LDS read in the loop the DMA goes out as inline assembly (see dma16: the
   // compiler would put a wait for all memory operations in front of those reads); otherwise
   // through the builtin, which the scheduling hints below can place.
   auto issue = [&](const bf16 *base, const auto &off, uint32_t step, int ni, char *stage, int i0, int i1) {
     constexpr int NOFF = sizeof(off) / sizeof(off[0]);
-    constexpr bool T = NOFF > 1;   // one offset per instruction: row-contiguous
     char *dst = stage + wave * (ni * 1024);
     if constexpr (AT || BT) {
       const dma_rsrc_t rs = dma_rsrc(base);
@@ -574,8 +570,9 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if (i < ni && i >= i0 && i < i1) {
-          if constexpr (T) dma16(rs, dst_addr + i * 1024, off[i < NOFF ? i : 0]);
-          else dma16(rs, dst_addr + i * 1024, off[0], i * step);
+          if constexpr (NOFF == 1) dma16(rs, dst_addr + i * 1024, off[0], i * step);
+          else if constexpr (NOFF == 2) dma16(rs, dst_addr + i * 1024, off[i & 1], (i >> 1) * step);
+          else dma16(rs, dst_addr + i * 1024, off[i < NOFF ? i : 0]);
         }
     } else {
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16 *>(base), 0, 0xFFFFFFFFu, 0x00020000);
@@ -619,6 +616,35 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
       return __builtin_bit_cast(bf16x8, v);
     }
   };
+  // Row-contiguous operand in a 256-row stage (32 units per k-row): tr_pos<32>(u, k) = u ^ mask(k), the mask is the
+  // same for every k-row a lane ever reads (k mod 4 and k bit 3 do not change with the k-step or the half), and
+  // the unit of block b of the wave tile is that of block 0 with 2 b in bits 1 .. 3, which block 0 leaves empty.
+  // So all of a lane's fragment addresses in a stage are ONE per-lane offset XOR a value that is the same in every
+  // lane (32 b, and the stage's offset, whose bits lie above), plus a constant: one address register per operand
+  // instead of one per block.  The uniform value passes through an empty asm statement so that the XOR stays
+  // inside the loop (hoisted, the eight results would occupy the registers this saves).
+  auto tr256_base = [&](int r0) -> uint32_t {   // block 0 at row r0 of the stage, k-step 0, low half
+    const int grp = lane >> 4, L = lane & 15;
+    const int nb = r0 + 4 * (L & 3), k = 8 * grp + (L >> 2);
+    return (uint32_t)(k * 512 + tr_pos<32>(nb >> 3, k) * 16 + (nb & 7) * 2);
+  };
+  typedef __attribute__((address_space(3))) const char *lds_ptr;
+  auto tr256_block = [&](uint32_t lane_off, uint32_t stage_off, int blk) -> lds_ptr {   // address of (block, k-step 0, low half)
+    uint32_t uni = stage_off ^ (uint32_t)(blk * 32);
+    asm volatile("" : "+s"(uni));
+    return (lds_ptr)(__attribute__((address_space(3))) const char *)smem + (lane_off ^ uni);
+  };
+  auto frag_tr256 = [&](lds_ptr block, int kk) -> bf16x8 {
+    typedef __attribute__((address_space(3))) i16x4 *lds_i16x4_ptr;
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(block + kk * (32 * 512)));
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(block + kk * (32 * 512) + 4 * 512));
+    i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+  constexpr bool A_TR256 = AT, B_TR256 = BT && BN == 256;
+  const uint32_t tr_a = A_TR256 ? tr256_base(wm * WM) : 0u, tr_b = B_TR256 ? tr256_base(wn * WN) : 0u;
+  // offset of a stage from the start of the rings (a multiple of 32 KB), the same in every lane
+  auto stage_offset = [&](const char *stage) { return (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(stage - smem)); };
   // A slab (two k-steps of 32) is four phases, one per pair of 16-row blocks of the wave tile; a phase issues both
   // k-steps of each of its 2 x TN accumulator blocks back to back.  Two consecutive MFMAs on one accumulator, and
   // beyond that consecutive MFMAs that share an operand, cost measurably less power than the same instructions
@@ -629,13 +655,26 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   bf16x8 bf[2][TN];     // B: [k-step][column block], all of the slab's
   auto read_aq = [&](const char *abuf, int q) {   // A fragments of phase q (q == 4: phase 0 of the next slab)
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < 2; ++rb) {
+      if constexpr (A_TR256) {
+        const lds_ptr block = tr256_block(tr_a, stage_offset(abuf), 2 * (q & 3) + rb);
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) aq[q & 1][rb][kk] = frag(abuf, wm * WM + (2 * (q & 3) + rb) * 16, kk, AT, BM);
+        for (int kk = 0; kk < 2; ++kk) aq[q & 1][rb][kk] = frag_tr256(block, kk);
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) aq[q & 1][rb][kk] = frag(abuf, wm * WM + (2 * (q & 3) + rb) * 16, kk, AT, BM);
+      }
+    }
   };
   auto read_bj = [&](const char *bbuf, int j) {
+    if constexpr (B_TR256) {
+      const lds_ptr block = tr256_block(tr_b, stage_offset(bbuf), j);
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) bf[kk][j] = frag(bbuf, wn * WN + j * 16, kk, BT, BN);
+      for (int kk = 0; kk < 2; ++kk) bf[kk][j] = frag_tr256(block, kk);
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) bf[kk][j] = frag(bbuf, wn * WN + j * 16, kk, BT, BN);
+    }
   };
   auto mfma_col = [&](int q, int j) {   // the 4 MFMAs of column block j in phase q
 #pragma unroll
@@ -753,8 +792,8 @@ __global__ __launch_bounds__(512, 1) void gemm_stream_kernel(GemmArgs g) {
   // The lane and wave numbers pass through an empty asm statement here: the epilogue's addresses then cannot be
   // computed ahead of the main loop, where they would occupy registers the loop needs (the 320-column tile has
   // 160 of 256 in accumulators).
-  int elane = lane, ewave = wave;
-  asm volatile("" : "+v"(elane), "+v"(ewave));
+  int elane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)), ewave = wave;
+  asm volatile("" : "+v"(elane), "+s"(ewave));
   const int ewm = ewave / WGN, ewn = ewave % WGN;
   constexpr int RP = WN == 80 ? 32 : 64;        // rows per pass
   constexpr int SEG = WN / 8;                   // 8-column segments per row
@@ -1055,9 +1094,7 @@ int gemm_mfma_pick_tile(int layout, int64_t M, int64_t N, int64_t K, bool have_w
     const bool small = tiles256 > 0 && tiles256 < 160 && !(have_workspace && plan_split(tiles256, nk, 256, 256, ~(size_t)0).tail > 0);
     if (!small || N % 256) {
       offer(GEMM_TILE_STREAM_256x256, 256, 256, 1.00, true);
-      // the wider tile does not fit the registers of the weight-gradient form (both operands through transposing
-      // reads: 13 address registers on top of 160 accumulators and 72 fragment registers)
-      if (layout != MTNLG_GEMM_TN) offer(GEMM_TILE_STREAM_256x320, 256, 320, GEMM_COST_256x320, false);
+      offer(GEMM_TILE_STREAM_256x320, 256, 320, GEMM_COST_256x320, false);
       if (pick >= 0) return pick;
     }
   }
