@@ -464,9 +464,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 //                for the first time: the weights); 160 KB.
 //     256 x 320: A two stages of 32 KB, B two of 40 KB; 144 KB.   N a multiple of 320.
 //   The wider tile moves 10 % fewer operand bytes per FLOP from L2 into LDS ((BM + BN) / (BM BN)), which is
-//   what holds the clock down under the board's power limit, and it covers the layer's forward and
-//   input-gradient shapes in whole rounds of 256 tiles; it pays with a ring one stage shorter and with 160 of
-//   a wave's 256 registers in accumulators (a 320 x 320 tile would need 200 and does not fit).
+//   what holds the clock down under the board's power limit, and it covers the layer's forward, input-gradient
+//   and FC weight-gradient shapes in whole rounds of 256 tiles; it pays with a ring one stage shorter and with
+//   160 of a wave's 256 registers in accumulators (a 320 x 320 tile would need 200 and does not fit), which
+//   leaves about 20 for addresses: hence the scalar DMA offsets and the XOR-derived fragment addresses below.
 //   The DMA instructions of a slab are spread over the phases of a slab so that the texture path never sees a burst.
 //   K-contiguous operand: stage = [ROWS][128 B], 16-byte chunk c of row r at chunk position
 //     c ^ (r & 7); MFMA fragments are 16-byte LDS reads (this placement measured conflict-free for the
@@ -477,10 +478,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 1) void gemm_bf16_kernel(GemmArgs g
 //     of a k-row permuted (tr_pos below) so that the fragment reads spread over all banks;
 //     MFMA fragments are two transposing 8-byte LDS reads (ds_read_b64_tr_b16: a 16-lane group reads
 //     4 k-rows x 16 rows and every lane receives the 4 k values of its own row).
-//   A slab is four phases: (k-step 0, first half of the wave tile's rows), (0, second half), (1, first),
-//   (1, second); each phase loads the fragments of the next one.  The one
-//   workgroup barrier per slab sits before the last phase (whose fragments are already in
-//   registers) so that the first fragment reads of the next slab hide behind a phase of MFMAs.
+//   A slab (two k-steps of 32) is four phases, one per pair of 16-row blocks of the wave tile, each issuing
+//   both k-steps of its 2 x TN accumulator blocks back to back and loading the A fragments of the next phase;
+//   the B fragments are held for the whole slab.  The one workgroup barrier per slab sits before the last
+//   phase (whose fragments are already in registers), which then reads the first A fragments and, block by
+//   block as its MFMAs release the registers, the B fragments of the next slab.
 //   Aligned problems only: M a multiple of BM, N of BN, K of 64.
 
 // Position of the 16-byte unit u of k-row k inside a row-contiguous stage's k-row of UPR units (an involution

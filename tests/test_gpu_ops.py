@@ -48,7 +48,7 @@ def test_gemm_plain(dtype, layout, shape):
 
 # Aligned shapes that take the streaming kernel whole, every element against the oracle: one and several slabs of K
 # (the DMA ring's prologue and its clamped look-ahead), one and several tiles of both tile widths (N a multiple of
-# 320 takes the 256 x 320 tile in the NT and NN forms), several row tiles.
+# 320 takes the 256 x 320 tile in all three forms), several row tiles.
 STREAM_SHAPES = [(256, 320, 64), (256, 640, 128), (512, 320, 192), (256, 256, 64), (512, 512, 128), (768, 960, 256)]
 
 
