@@ -73,6 +73,21 @@ def test_gemm_streaming_kernel_small_aligned_shapes(layout, shape):
     assert_close(C32, want, TOL["fp32"], f"stream {layout} {shape} f32 out")
 
 
+@pytest.mark.parametrize("shape", [(256, 320, 128), (512, 256, 64), (264, 520, 328)])
+def test_gemm_fused_activation_backward_at_fp32_accuracy(shape):
+    """The MFMA GEMMs evaluate GeLU and GeLU' through the hardware exp2 and reciprocal (s = 1 / (1 + exp(-2u))) rather
+    than the library tanh.  With fp32 output nothing is rounded to bf16 after the activation's derivative, so the
+    product times GeLU'(aux) has to meet the fp32 bar: that pins the fast form to a few 1e-7, four orders below
+    what the bf16 cases can see.  aux spans the whole range, including very negative values where 1 + tanh cancels."""
+    Mm, N, K = shape
+    A, W = randn((Mm, K), "bf16", 91), randn((N, K), "bf16", 92, 0.2)
+    z = (torch.linspace(-14.0, 14.0, Mm * N).reshape(Mm, N) + randn((Mm, N), "bf16", 93, 0.5).float()).bfloat16()
+    C32 = torch.full((Mm, N), float("nan"), dtype=torch.float32, device="cuda")
+    M.mtnlg_gemm(B.GEMM_NT, dev(A), dev(W), C32, aux=dev(z), epilogue=B.EPI_GELU_GRAD | B.EPI_OUT_F32)
+    want = gemm_oracle(B.GEMM_NT, A, W) * oracle.gelu_grad(to_np(z))
+    assert_close(C32, want, TOL["fp32"], f"gelu grad f32 out {shape}")
+
+
 @pytest.mark.parametrize("layout", [B.GEMM_NT, B.GEMM_NN, B.GEMM_TN])
 @pytest.mark.parametrize("shape", [(520, 776, 4104), (256, 512, 2048)])
 def test_gemm_split_k_tail_with_workspace(layout, shape):
